@@ -1,0 +1,224 @@
+"""CPU oracle for parallel prefix verification -- TEST INFRASTRUCTURE ONLY.
+
+Plain, slow, fp64 numpy.  Only tests, the smoke check and the benchmark's CPU
+baseline may import this file; the product (the HIP library and its Python
+binding) never does, and this file imports nothing from the product.
+
+What it computes, and the passages it follows (paper section "Parallel Prefix
+Verification", and appendix "Detailed Algorithm": "Notation and judge
+calibration", "Parallel partial verify", "Adopted-prefix length"):
+
+* `dense_mask`      the custom attention mask of the packed verification pass,
+                    materialised entry by entry from the visibility rules of
+                    "Parallel Prefix Verification".
+* `positions`       rotary positions: prompt and draft count up from 0; suffix
+                    copy k continues from the end of the prefix it judges, so
+                    that its judgment position "sees exactly the input" of a
+                    stand-alone run of (prefix, suffix).
+* `rope`            rotary embedding, half-split pairing.
+* `attention`       softmax(mask(Q K^T * scale)) V for one request, no tiling.
+* `first_reject`    two-way confidence verdicts (Eq. for p_2w), the last-correct
+                    index k* ("Parallel partial verify"), the adopted length L*
+                    (Eq. "adopted", with rollback eta = 0 generalised to arbitrary
+                    boundaries) and the main-text rule t* = max{t_i : Correct}.
+
+Readings where the paper is silent are listed in the design notes of this
+repository; every function below is pinned by tests that do not reuse its
+own formula (brute force over stand-alone sequences with a library attention,
+closed-form counts, exhaustive enumeration).
+
+Conventions (0-indexed).  One request has P prompt tokens, T draft tokens and
+K suffix copies ("segments") of S tokens each, laid out
+[prompt | draft | segment_0 | ... | segment_{K-1}], N = P + T + K*S tokens.
+`boundaries[k] = p_k` is the number of draft tokens segment k may see.
+"""
+from __future__ import annotations
+
+import math
+from typing import Optional, Sequence
+
+import numpy as np
+
+
+# --------------------------------------------------------------------------- mask
+
+def dense_mask(P: int, T: int, S: int, boundaries: Sequence[int],
+               rows: Optional[Sequence[int]] = None) -> np.ndarray:
+    """M[r, j] = 1 iff query token rows[r] may attend to key token j (uint8).
+
+    Rules ("Parallel Prefix Verification"):
+      * a prompt or draft token attends causally (to itself and everything before);
+      * a token of suffix copy k attends to the whole prompt, to the draft tokens
+        up through its boundary (the first p_k of them), causally to its own copy,
+        and to nothing else -- never to another copy, never to later draft tokens.
+    """
+    K = len(boundaries)
+    N = P + T + K * S
+    if rows is None:
+        rows = range(N)
+    j = np.arange(N)
+    key_is_prompt = j < P
+    key_is_draft = (j >= P) & (j < P + T)
+    key_draft_index = j - P                      # meaningful where key_is_draft
+    key_is_segment = j >= P + T
+    key_segment = np.where(key_is_segment, (j - P - T) // max(S, 1), -1)
+    key_offset = np.where(key_is_segment, (j - P - T) % max(S, 1), -1)
+
+    M = np.zeros((len(rows), N), dtype=np.uint8)
+    for r, i in enumerate(rows):
+        if i < P + T:
+            visible = j <= i
+        else:
+            k = (i - P - T) // S
+            a = (i - P - T) % S
+            sees_prompt = key_is_prompt
+            sees_draft = key_is_draft & (key_draft_index < boundaries[k])
+            sees_self = key_is_segment & (key_segment == k) & (key_offset <= a)
+            visible = sees_prompt | sees_draft | sees_self
+        M[r] = visible
+    return M
+
+
+def positions(P: int, T: int, S: int, boundaries: Sequence[int]) -> np.ndarray:
+    """Rotary position of every token (int64 [N])."""
+    K = len(boundaries)
+    pos = np.empty(P + T + K * S, dtype=np.int64)
+    pos[:P + T] = np.arange(P + T)
+    for k in range(K):
+        start = P + T + k * S
+        pos[start:start + S] = P + boundaries[k] + np.arange(S)
+    return pos
+
+
+def judge_rows(P: int, T: int, S: int, K: int) -> np.ndarray:
+    """Row whose hidden state carries the verdict of segment k: its last token."""
+    return np.array([P + T + (k + 1) * S - 1 for k in range(K)], dtype=np.int64)
+
+
+# --------------------------------------------------------------------------- rotary
+
+def rope(x: np.ndarray, pos: np.ndarray, theta: float) -> np.ndarray:
+    """Rotate x [N, H, D] (fp64) by angle pos * theta^(-2c/D) on the pair (c, c + D/2)."""
+    if theta == 0.0:
+        return x.copy()
+    N, H, D = x.shape
+    half = D // 2
+    c = np.arange(half, dtype=np.float64)
+    inv_freq = theta ** (-2.0 * c / D)
+    phi = pos.astype(np.float64)[:, None] * inv_freq[None, :]        # [N, half]
+    cos = np.cos(phi)[:, None, :]
+    sin = np.sin(phi)[:, None, :]
+    lo, hi = x[..., :half], x[..., half:]
+    out = np.empty_like(x)
+    out[..., :half] = lo * cos - hi * sin
+    out[..., half:] = hi * cos + lo * sin
+    return out
+
+
+# --------------------------------------------------------------------------- attention
+
+def attention(q: np.ndarray, k: np.ndarray, v: np.ndarray, mask: np.ndarray,
+              scale: Optional[float] = None, rows: Optional[Sequence[int]] = None,
+              return_lse: bool = False):
+    """Masked softmax attention of one request in fp64.
+
+    q [N, Hq, D], k and v [N, Hkv, D] (already rotated), mask [len(rows), N] for the
+    query rows `rows` (all rows if None).  Query head h uses kv head h // (Hq/Hkv).
+    Returns O [len(rows), Hq, D] (and the natural-log normaliser [len(rows), Hq]).
+    """
+    N, Hq, D = q.shape
+    Hkv = k.shape[1]
+    G = Hq // Hkv
+    if scale is None:
+        scale = 1.0 / math.sqrt(D)
+    if rows is None:
+        rows = np.arange(N)
+    rows = np.asarray(rows, dtype=np.int64)
+    out = np.empty((len(rows), Hq, D), dtype=np.float64)
+    lse = np.empty((len(rows), Hq), dtype=np.float64)
+    allowed = mask.astype(bool)
+    for h in range(Hq):
+        g = h // G
+        s = (q[rows, h, :] @ k[:, g, :].T) * scale                  # [R, N]
+        s = np.where(allowed, s, -np.inf)
+        m = s.max(axis=1, keepdims=True)
+        e = np.exp(s - m)
+        denom = e.sum(axis=1, keepdims=True)
+        out[:, h, :] = (e @ v[:, g, :]) / denom
+        lse[:, h] = (m + np.log(denom))[:, 0]
+    return (out, lse) if return_lse else out
+
+
+def masked_attention(prompt_len, draft_len, num_segments, segment_len, boundaries,
+                     q: np.ndarray, k: np.ndarray, v: np.ndarray, rope_theta: float = 0.0,
+                     scale: Optional[float] = None, rows_per_request=None, return_lse: bool = False):
+    """The packed pass: every request of the batch, tokens concatenated request after request.
+
+    `boundaries` is a list of per-request lists.  q/k/v hold the same values the GPU is
+    given, widened to fp64.  `rows_per_request[b]` (optional) restricts request b to the
+    listed local query rows; the outputs are then concatenated in that order.
+    """
+    outs, lses = [], []
+    start = 0
+    for b in range(len(prompt_len)):
+        P, T, K, S = prompt_len[b], draft_len[b], num_segments[b], segment_len[b]
+        N = P + T + K * S
+        rows = None if rows_per_request is None else rows_per_request[b]
+        pos = positions(P, T, S, boundaries[b])
+        qb = rope(np.asarray(q[start:start + N], dtype=np.float64), pos, rope_theta)
+        kb = rope(np.asarray(k[start:start + N], dtype=np.float64), pos, rope_theta)
+        vb = np.asarray(v[start:start + N], dtype=np.float64)
+        M = dense_mask(P, T, S, boundaries[b], rows)
+        o, l = attention(qb, kb, vb, M, scale, rows, return_lse=True)
+        outs.append(o)
+        lses.append(l)
+        start += N
+    O = np.concatenate(outs, axis=0)
+    return (O, np.concatenate(lses, axis=0)) if return_lse else O
+
+
+# --------------------------------------------------------------------------- readout
+
+def margin_threshold(tau: float) -> float:
+    """Smallest logit margin l_C - l_I whose two-way confidence reaches tau."""
+    return math.log(tau / (1.0 - tau))
+
+
+def verdicts(logits: np.ndarray, threshold: float) -> np.ndarray:
+    """Correct (True) iff the raw argmax is Correct (ties count as Correct) and the
+    two-way confidence is at least tau, i.e. the fp64 margin reaches the threshold."""
+    d = logits[:, 0].astype(np.float64) - logits[:, 1].astype(np.float64)
+    return (d >= 0.0) & (d >= threshold)
+
+
+def first_reject(logits: np.ndarray, num_segments: Sequence[int], boundaries, threshold: float,
+                 mode: int = 0) -> np.ndarray:
+    """Per request (first_reject, k_star, L_star, n_incorrect), int32 [B, 4].
+
+    mode 0 ("Parallel partial verify"): k* is the largest k whose verdict is Correct with no
+      Incorrect before it, so first_reject = k* + 1 is the first Incorrect index (K if none);
+      L* is the boundary of chunk k* (0 when k* = -1, the restart case).
+    mode 1 (main text): t* = max{t_i : prefix i is Correct}; k* is the index attaining it
+      (the largest such index), first_reject is still the first Incorrect index.
+    """
+    out = np.zeros((len(num_segments), 4), dtype=np.int32)
+    start = 0
+    for b, K in enumerate(num_segments):
+        ok = verdicts(logits[start:start + K], threshold)
+        p = list(boundaries[b])
+        first = K
+        for kk in range(K):
+            if not ok[kk]:
+                first = kk
+                break
+        if mode == 0:
+            k_star = first - 1
+        else:
+            k_star = -1
+            for kk in range(K):
+                if ok[kk]:
+                    k_star = kk
+        L_star = p[k_star] if k_star >= 0 else 0
+        out[b] = (first, k_star, L_star, int(K - ok.sum()))
+        start += K
+    return out
