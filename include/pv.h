@@ -1,0 +1,149 @@
+/* pv.h -- C ABI of the parallel-prefix-verification attention library (AMD MI355X, gfx950).
+ *
+ * The library evaluates, for one transformer layer, the attention of the single forward pass
+ * in which K short suffix copies ("segments") are appended after a full draft and judged at
+ * once (paper section "Parallel Prefix Verification"): prompt and draft tokens attend causally;
+ * segment k attends to the prompt, to the first p_k draft tokens, and causally to itself,
+ * never to another segment; its rotary positions continue from the end of the prefix it
+ * judges.  A readout turns the per-segment Correct/Incorrect logits into the maximal valid
+ * prefix (appendix "Notation and judge calibration", "Parallel partial verify",
+ * "Adopted-prefix length").
+ *
+ * Conventions shared by every entry point
+ *   Layout     Packed variable length: the tokens of all requests are concatenated; request b
+ *              owns rows [tok_start[b], tok_start[b+1]) in the order
+ *              [prompt | draft | segment_0 | ... | segment_{K-1}].  Q and O are
+ *              [total_tokens][Hq][D], K and V are [total_tokens][Hkv][D], innermost contiguous,
+ *              base pointers 16-byte aligned.
+ *   Memory     "host" pointers are ordinary CPU memory read only during the call.  "device"
+ *              pointers are GPU memory owned by the caller (e.g. a torch tensor); the library
+ *              never allocates or frees device memory, never synchronises, never creates
+ *              streams.  All GPU work is enqueued on the caller's stream (a hipStream_t passed
+ *              as void*; NULL = the default stream) and outputs are valid once that stream
+ *              has reached the end of the enqueued work.
+ *   Errors     Every call returns a pv_status.  Argument errors are detected on the host
+ *              before anything is launched (nothing has been enqueued when an error other
+ *              than PV_ERR_HIP is returned).  A failing HIP call maps to PV_ERR_HIP and the
+ *              raw hipError_t is kept per thread for pv_last_hip_error().
+ *   Determinism Fixed tile order and no atomics: results are bit-identical run to run.
+ */
+#ifndef PV_H_
+#define PV_H_
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef int32_t pv_status;
+enum {
+  PV_OK = 0,
+  PV_ERR_NULL = -1,       /* a required pointer is NULL */
+  PV_ERR_SHAPE = -2,      /* bad batch / lengths / head counts / head_dim / sizes struct */
+  PV_ERR_BOUNDARY = -3,   /* boundaries not non-decreasing or outside [0, T] */
+  PV_ERR_WORKSPACE = -4,  /* plan / mask / workspace buffer smaller than pv_query_sizes says */
+  PV_ERR_ALIGN = -5,      /* a device pointer is not 16-byte aligned */
+  PV_ERR_DTYPE = -6,      /* unsupported dtype combination */
+  PV_ERR_ARCH = -7,       /* current device is not gfx950 */
+  PV_ERR_HIP = -8         /* a HIP runtime call failed, see pv_last_hip_error() */
+};
+
+enum { PV_BF16 = 0, PV_F32 = 1 };
+
+/* Structure of a packed verification batch.  HOST memory, owned by the caller. */
+typedef struct {
+  int32_t batch;                 /* B >= 1 */
+  const int32_t* prompt_len;     /* [B]  P_b >= 0 */
+  const int32_t* draft_len;      /* [B]  T_b >= 1 */
+  const int32_t* num_segments;   /* [B]  K_b >= 0   (0 => plain causal attention) */
+  const int32_t* segment_len;    /* [B]  S_b >= 1   (same for all segments of a request) */
+  const int32_t* boundaries;     /* [sum K_b] p_k = number of draft tokens segment k sees;
+                                    per request non-decreasing and 0 <= p_k <= T_b */
+} pv_problem;
+
+/* Sizes derived from a pv_problem; filled by pv_query_sizes, passed back to the other calls. */
+typedef struct {
+  int64_t batch;
+  int64_t total_tokens;          /* sum_b (P_b + T_b + K_b * S_b) */
+  int64_t total_segments;        /* sum_b K_b */
+  int64_t max_seq_len;           /* max_b N_b */
+  int64_t n_q_tiles;             /* work items per kv head */
+  int64_t padded_keys;           /* sum_b N_b rounded up to the key tile */
+  int64_t plan_bytes;            /* device bytes pv_build_mask writes */
+  int64_t dense_mask_bytes;      /* sum_b N_b^2 (uint8), only if the dense mask is requested */
+  int64_t attn_workspace_bytes;  /* device scratch pv_masked_attention needs */
+  int32_t n_q_heads, n_kv_heads, head_dim, in_dtype;
+  int32_t tile_m, tile_n;        /* query tokens per work item, keys per tile */
+  int32_t reserved[2];
+} pv_sizes;
+
+/* Host only: validates the problem and the head configuration and fills `out`.
+ * Supported: head_dim 64 or 128, Hq a multiple of Hkv with Hq/Hkv <= 8, in_dtype PV_BF16
+ * (MFMA path) or PV_F32 (debug path). */
+pv_status pv_query_sizes(const pv_problem* problem, int32_t n_q_heads, int32_t n_kv_heads,
+                         int32_t head_dim, int32_t in_dtype, pv_sizes* out);
+
+/* The prefix attention mask of "Parallel Prefix Verification" as a device-resident plan:
+ * per token its rotary position and the row descriptor (a_end, b_start) such that key j of the
+ * same request is visible to query i iff j < a_end or b_start <= j <= i; per segment the row
+ * that carries its verdict (its last token); and the list of query tiles with the key-tile
+ * ranges that contain at least one visible pair (fully masked tiles are never listed), ordered
+ * longest first.
+ *   problem         host, validated again here
+ *   plan_dev        device, >= sizes->plan_bytes, 16-byte aligned; opaque, position independent
+ *   dense_mask_dev  device or NULL.  If given, also writes the mask entry by entry (uint8 0/1,
+ *                   request b at byte offset sum_{b'<b} N_b'^2, row-major [N_b][N_b]); meant
+ *                   for tests, sizes->dense_mask_bytes bytes. */
+pv_status pv_build_mask(const pv_problem* problem, const pv_sizes* sizes, void* plan_dev,
+                        int64_t plan_bytes, uint8_t* dense_mask_dev, int64_t dense_mask_bytes,
+                        void* stream);
+
+/* O = softmax(mask(Q K^T * scale)) V under the plan's mask, with rotary embedding applied to Q
+ * and K at the plan's positions (angle pos * theta^(-2c/D) on the pair (c, c + D/2)).
+ *   q, k, v          device, in_dtype, layout above; not modified
+ *   out              device, out_dtype, [total_tokens][Hq][D]
+ *   lse              device or NULL: natural-log softmax normaliser, float [Hq][total_tokens]
+ *   in_dtype/out_dtype  PV_BF16 in -> PV_BF16 or PV_F32 out (bf16 MFMA, fp32 accumulate);
+ *                       PV_F32 in  -> PV_F32 out (fp32 debug path)
+ *   softmax_scale    0 => 1/sqrt(D)
+ *   rope_theta       0 => no rotation
+ *   workspace        device scratch, >= sizes->attn_workspace_bytes, 16-byte aligned */
+pv_status pv_masked_attention(const pv_sizes* sizes, const void* plan_dev, const void* q,
+                              const void* k, const void* v, void* out, float* lse,
+                              int32_t out_dtype, float softmax_scale, float rope_theta,
+                              void* workspace, int64_t workspace_bytes, void* stream);
+
+/* Readout.  Verdict of segment k is Correct iff l_C >= l_I and l_C - l_I >= margin_threshold
+ * (margin_threshold = ln(tau / (1 - tau)) makes this the two-way-confidence rule p_2w >= tau),
+ * compared in fp64.  Per request writes int32 (first_reject, k_star, L_star, n_incorrect):
+ *   first_reject  index of the first Incorrect segment, K_b if none
+ *   mode 0        k_star = first_reject - 1 (largest Correct index with no Incorrect before it)
+ *   mode 1        k_star = largest Correct index (t* = max{t_i : Correct} of the main text)
+ *   L_star        boundary p_{k_star}, 0 if k_star = -1 (restart from scratch)
+ *   logits_dev    device float [total_segments][2] = (l_C, l_I), segment order of the problem
+ *   out_dev       device int32 [B][4] */
+pv_status pv_first_reject(const pv_sizes* sizes, const void* plan_dev, const float* logits_dev,
+                          double margin_threshold, int32_t mode, int32_t* out_dev, void* stream);
+
+/* Copies of the plan's per-token / per-segment arrays for inspection (device to device, on
+ * `stream`): positions, a_end, b_start are int32 [total_tokens]; judge_row is int32
+ * [total_segments] (row index into the packed token dimension).  Any output may be NULL. */
+pv_status pv_plan_export(const pv_sizes* sizes, const void* plan_dev, int32_t* positions_dev,
+                         int32_t* a_end_dev, int32_t* b_start_dev, int32_t* judge_row_dev,
+                         void* stream);
+
+/* Profiling aid for benchmarks: when enabled, pv_masked_attention brackets its main attention
+ * kernel with HIP events on the caller's stream.  pv_profile_read waits for the latest pair and
+ * returns the kernel's duration in milliseconds (PV_ERR_SHAPE if nothing was recorded). */
+pv_status pv_profile_enable(int32_t on);
+pv_status pv_profile_read(float* main_kernel_ms);
+
+const char* pv_strerror(pv_status status);
+int32_t pv_last_hip_error(void);
+const char* pv_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PV_H_ */

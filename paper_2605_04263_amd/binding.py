@@ -1,0 +1,223 @@
+"""Thin ctypes binding of libpv.so (see include/pv.h).
+
+Argument marshalling only: torch tensors supply device memory and the current stream; every
+step of the path runs in the library's HIP kernels.  There is no CPU fallback: if the shared
+library is missing, importing this module fails.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import math
+import os
+from dataclasses import dataclass
+from typing import Optional, Sequence
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libpv.so")
+
+PV_OK = 0
+PV_ERR_NULL, PV_ERR_SHAPE, PV_ERR_BOUNDARY, PV_ERR_WORKSPACE = -1, -2, -3, -4
+PV_ERR_ALIGN, PV_ERR_DTYPE, PV_ERR_ARCH, PV_ERR_HIP = -5, -6, -7, -8
+PV_BF16, PV_F32 = 0, 1
+
+
+class PvProblem(C.Structure):
+    _fields_ = [("batch", C.c_int32),
+                ("prompt_len", C.POINTER(C.c_int32)),
+                ("draft_len", C.POINTER(C.c_int32)),
+                ("num_segments", C.POINTER(C.c_int32)),
+                ("segment_len", C.POINTER(C.c_int32)),
+                ("boundaries", C.POINTER(C.c_int32))]
+
+
+class PvSizes(C.Structure):
+    _fields_ = [("batch", C.c_int64), ("total_tokens", C.c_int64), ("total_segments", C.c_int64),
+                ("max_seq_len", C.c_int64), ("n_q_tiles", C.c_int64), ("padded_keys", C.c_int64),
+                ("plan_bytes", C.c_int64), ("dense_mask_bytes", C.c_int64),
+                ("attn_workspace_bytes", C.c_int64),
+                ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32),
+                ("in_dtype", C.c_int32), ("tile_m", C.c_int32), ("tile_n", C.c_int32),
+                ("reserved", C.c_int32 * 2)]
+
+
+def _load() -> C.CDLL:
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is not built: run `python -c 'import __graft_entry__ as g; g.build()'`")
+    lib = C.CDLL(LIB_PATH)
+    P = C.POINTER
+    lib.pv_query_sizes.argtypes = [P(PvProblem), C.c_int32, C.c_int32, C.c_int32, C.c_int32, P(PvSizes)]
+    lib.pv_build_mask.argtypes = [P(PvProblem), P(PvSizes), C.c_void_p, C.c_int64, C.c_void_p,
+                                  C.c_int64, C.c_void_p]
+    lib.pv_masked_attention.argtypes = [P(PvSizes), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                        C.c_void_p, C.c_void_p, C.c_int32, C.c_float, C.c_float,
+                                        C.c_void_p, C.c_int64, C.c_void_p]
+    lib.pv_first_reject.argtypes = [P(PvSizes), C.c_void_p, C.c_void_p, C.c_double, C.c_int32,
+                                    C.c_void_p, C.c_void_p]
+    lib.pv_plan_export.argtypes = [P(PvSizes), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                   C.c_void_p, C.c_void_p]
+    lib.pv_profile_enable.argtypes = [C.c_int32]
+    lib.pv_profile_read.argtypes = [P(C.c_float)]
+    for name in ("pv_query_sizes", "pv_build_mask", "pv_masked_attention", "pv_first_reject",
+                 "pv_plan_export", "pv_profile_enable", "pv_profile_read", "pv_last_hip_error"):
+        getattr(lib, name).restype = C.c_int32
+    lib.pv_strerror.argtypes = [C.c_int32]
+    lib.pv_strerror.restype = C.c_char_p
+    lib.pv_version.restype = C.c_char_p
+    return lib
+
+
+lib = _load()
+
+
+class PvError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        msg = lib.pv_strerror(status).decode()
+        if status == PV_ERR_HIP:
+            msg += f" [hipError {lib.pv_last_hip_error()}]"
+        super().__init__(f"{where}: {msg} ({status})")
+
+
+def _check(status: int, where: str) -> None:
+    if status != PV_OK:
+        raise PvError(status, where)
+
+
+def _i32(values: Sequence[int]):
+    return (C.c_int32 * max(1, len(values)))(*values)
+
+
+@dataclass
+class HostProblem:
+    """Keeps the ctypes arrays of a pv_problem alive."""
+    struct: PvProblem
+    keep: tuple
+
+
+def make_problem(prompt_len: Sequence[int], draft_len: Sequence[int], num_segments: Sequence[int],
+                 segment_len: Sequence[int], boundaries: Sequence[int]) -> HostProblem:
+    arrs = tuple(_i32(list(x)) for x in (prompt_len, draft_len, num_segments, segment_len, boundaries))
+    s = PvProblem(len(prompt_len), *[C.cast(a, C.POINTER(C.c_int32)) for a in arrs])
+    return HostProblem(s, arrs)
+
+
+def pv_query_sizes(problem: HostProblem, n_q_heads: int, n_kv_heads: int, head_dim: int,
+                   in_dtype: int) -> PvSizes:
+    out = PvSizes()
+    _check(lib.pv_query_sizes(C.byref(problem.struct), n_q_heads, n_kv_heads, head_dim, in_dtype,
+                              C.byref(out)), "pv_query_sizes")
+    return out
+
+
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    if t is None:
+        return None
+    if not t.is_contiguous():
+        raise ValueError("tensor must be contiguous")
+    return t.data_ptr()
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def pv_build_mask(problem: HostProblem, sizes: PvSizes, plan: torch.Tensor,
+                  dense_mask: Optional[torch.Tensor] = None) -> None:
+    """Writes the plan (and optionally the uint8 dense mask) on the current stream."""
+    _check(lib.pv_build_mask(C.byref(problem.struct), C.byref(sizes), _ptr(plan),
+                             plan.numel() * plan.element_size(), _ptr(dense_mask),
+                             0 if dense_mask is None else dense_mask.numel(), _stream()),
+           "pv_build_mask")
+
+
+def pv_masked_attention(sizes: PvSizes, plan: torch.Tensor, q: torch.Tensor, k: torch.Tensor,
+                        v: torch.Tensor, out: torch.Tensor, workspace: torch.Tensor,
+                        lse: Optional[torch.Tensor] = None, softmax_scale: float = 0.0,
+                        rope_theta: float = 0.0) -> None:
+    want = torch.float32 if sizes.in_dtype == PV_F32 else torch.bfloat16
+    if q.dtype != want or k.dtype != want or v.dtype != want:
+        raise ValueError("q/k/v dtype does not match sizes.in_dtype")
+    n, hq, hkv, d = sizes.total_tokens, sizes.n_q_heads, sizes.n_kv_heads, sizes.head_dim
+    if tuple(q.shape) != (n, hq, d) or tuple(k.shape) != (n, hkv, d) or tuple(v.shape) != (n, hkv, d) \
+            or tuple(out.shape) != (n, hq, d):
+        raise ValueError("q/k/v/out shapes do not match sizes")
+    if lse is not None and (lse.dtype != torch.float32 or tuple(lse.shape) != (hq, n)):
+        raise ValueError("lse must be float32 [Hq, total_tokens]")
+    if out.dtype == torch.bfloat16:
+        out_dtype = PV_BF16
+    elif out.dtype == torch.float32:
+        out_dtype = PV_F32
+    else:
+        raise ValueError("out must be bf16 or fp32")
+    _check(lib.pv_masked_attention(C.byref(sizes), _ptr(plan), _ptr(q), _ptr(k), _ptr(v), _ptr(out),
+                                   _ptr(lse), out_dtype, softmax_scale, rope_theta, _ptr(workspace),
+                                   workspace.numel() * workspace.element_size(), _stream()),
+           "pv_masked_attention")
+
+
+def pv_first_reject(sizes: PvSizes, plan: torch.Tensor, logits: torch.Tensor, margin_threshold: float,
+                    mode: int, out: torch.Tensor) -> None:
+    if logits.dtype != torch.float32 or tuple(logits.shape) != (sizes.total_segments, 2):
+        raise ValueError("logits must be float32 [total_segments, 2]")
+    if out.dtype != torch.int32 or tuple(out.shape) != (sizes.batch, 4):
+        raise ValueError("out must be int32 [batch, 4]")
+    _check(lib.pv_first_reject(C.byref(sizes), _ptr(plan), _ptr(logits) if logits.numel() else None,
+                               margin_threshold, mode, _ptr(out), _stream()), "pv_first_reject")
+
+
+def pv_plan_export(sizes: PvSizes, plan: torch.Tensor):
+    """(positions, a_end, b_start, judge_row) as int32 device tensors."""
+    dev = plan.device
+    n, ns = sizes.total_tokens, sizes.total_segments
+    pos, ae, bs = (torch.empty(n, dtype=torch.int32, device=dev) for _ in range(3))
+    jr = torch.empty(max(ns, 1), dtype=torch.int32, device=dev)
+    _check(lib.pv_plan_export(C.byref(sizes), _ptr(plan), _ptr(pos), _ptr(ae), _ptr(bs), _ptr(jr),
+                              _stream()), "pv_plan_export")
+    return pos, ae, bs, jr[:ns]
+
+
+def pv_profile_enable(on: bool) -> None:
+    _check(lib.pv_profile_enable(1 if on else 0), "pv_profile_enable")
+
+
+def pv_profile_read() -> float:
+    ms = C.c_float(0.0)
+    _check(lib.pv_profile_read(C.byref(ms)), "pv_profile_read")
+    return ms.value
+
+
+def margin_from_tau(tau: float) -> float:
+    """ln(tau / (1 - tau)): the margin at which the two-way confidence equals tau."""
+    return math.log(tau / (1.0 - tau))
+
+
+class Verifier:
+    """Convenience holder of the device buffers of one problem (plan, workspace)."""
+
+    def __init__(self, prompt_len, draft_len, num_segments, segment_len, boundaries_flat,
+                 n_q_heads: int, n_kv_heads: int, head_dim: int, dtype: torch.dtype,
+                 device: str = "cuda:0", dense_mask: bool = False):
+        self.problem = make_problem(prompt_len, draft_len, num_segments, segment_len, boundaries_flat)
+        in_dtype = PV_F32 if dtype == torch.float32 else PV_BF16
+        self.sizes = pv_query_sizes(self.problem, n_q_heads, n_kv_heads, head_dim, in_dtype)
+        self.device = torch.device(device)
+        self.plan = torch.empty(self.sizes.plan_bytes // 4, dtype=torch.int32, device=self.device)
+        self.workspace = torch.empty(self.sizes.attn_workspace_bytes, dtype=torch.uint8, device=self.device)
+        self.dense_mask = (torch.empty(self.sizes.dense_mask_bytes, dtype=torch.uint8, device=self.device)
+                           if dense_mask else None)
+        self.readout = torch.empty(self.sizes.batch, 4, dtype=torch.int32, device=self.device)
+
+    def build_mask(self) -> None:
+        pv_build_mask(self.problem, self.sizes, self.plan, self.dense_mask)
+
+    def attention(self, q, k, v, out=None, lse=None, softmax_scale: float = 0.0, rope_theta: float = 0.0):
+        if out is None:
+            out = torch.empty_like(q)
+        pv_masked_attention(self.sizes, self.plan, q, k, v, out, self.workspace, lse, softmax_scale, rope_theta)
+        return out
+
+    def first_reject(self, logits, margin_threshold: float, mode: int = 0):
+        pv_first_reject(self.sizes, self.plan, logits, margin_threshold, mode, self.readout)
+        return self.readout

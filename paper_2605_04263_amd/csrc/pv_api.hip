@@ -1,0 +1,379 @@
+// C ABI of the library: argument validation on the host, then kernel launches on the caller's
+// stream.  Nothing here allocates device memory or synchronises (pv_profile_read excepted).
+#include <cmath>
+#include <cstring>
+#include <vector>
+
+#include "pv_internal.h"
+
+namespace pv {
+
+static thread_local int32_t g_last_hip = 0;
+static bool g_profile = false;
+static hipEvent_t g_ev0 = nullptr, g_ev1 = nullptr;
+static bool g_ev_recorded = false;
+
+static inline pv_status hip_fail(hipError_t e) {
+  g_last_hip = (int32_t)e;
+  return PV_ERR_HIP;
+}
+
+static inline int64_t align_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
+
+void plan_layout(int batch, int64_t total_tokens, int64_t total_segments, int64_t n_q_tiles,
+                 int64_t padded_keys, PlanHeader* h) {
+  std::memset(h, 0, sizeof(*h));
+  h->magic = kPlanMagic;
+  h->batch = batch;
+  h->total_tokens = (int32_t)total_tokens;
+  h->total_segments = (int32_t)total_segments;
+  h->n_q_tiles = (int32_t)n_q_tiles;
+  h->tile_m = kTileM;
+  h->tile_n = kTileN;
+  h->padded_keys = (int32_t)padded_keys;
+  int64_t o = sizeof(PlanHeader) / 4;
+  auto take = [&](int64_t n) { int64_t r = o; o = align_up(o + n, 4); return (int32_t)r; };
+  h->off_prompt = take(batch);
+  h->off_draft = take(batch);
+  h->off_nseg = take(batch);
+  h->off_seglen = take(batch);
+  h->off_tok_start = take(batch + 1);
+  h->off_seg_start = take(batch + 1);
+  h->off_qtile_start = take(batch + 1);
+  h->off_kpad_start = take(batch + 1);
+  h->off_mask_start = take(2 * (int64_t)(batch + 1));
+  h->off_bounds = take(total_segments);
+  h->off_device_begin = (int32_t)o;
+  h->off_pos = take(total_tokens);
+  h->off_aend = take(total_tokens);
+  h->off_bstart = take(total_tokens);
+  h->off_judge = take(total_segments);
+  h->off_tiles = take(n_q_tiles * 8);
+  h->off_work = take(n_q_tiles * 8);
+  h->total_ints = (int32_t)o;
+}
+
+AttnWorkspace attn_workspace_layout(int64_t total_tokens, int64_t padded_keys, int hkv, int d,
+                                    int in_dtype) {
+  AttnWorkspace w;
+  int64_t o = 0;
+  w.off_cs = o;
+  o = align_up(o + total_tokens * (d / 2) * 8, 256);
+  w.off_krot = o;
+  if (in_dtype == PV_BF16) {
+    o = align_up(o + (int64_t)hkv * padded_keys * d * 2, 256);
+    w.off_vt = o;
+    o = align_up(o + (int64_t)hkv * padded_keys * d * 2, 256);
+  } else {
+    o = align_up(o + total_tokens * hkv * d * 4, 256);
+    w.off_vt = o;
+  }
+  w.total = o;
+  return w;
+}
+
+struct Totals {
+  int64_t tokens = 0, segments = 0, max_len = 0, q_tiles = 0, padded_keys = 0, mask_bytes = 0;
+};
+
+// Validates the problem; fills totals.  Limits keep every index inside int32.
+static pv_status validate_problem(const pv_problem* p, Totals* t) {
+  if (!p) return PV_ERR_NULL;
+  if (p->batch < 1 || p->batch > (1 << 20)) return PV_ERR_SHAPE;
+  if (!p->prompt_len || !p->draft_len || !p->num_segments || !p->segment_len) return PV_ERR_NULL;
+  int64_t nseg = 0;
+  for (int b = 0; b < p->batch; ++b) {
+    if (p->num_segments[b] < 0) return PV_ERR_SHAPE;
+    nseg += p->num_segments[b];
+  }
+  if (nseg > 0 && !p->boundaries) return PV_ERR_NULL;
+  int64_t seg = 0;
+  for (int b = 0; b < p->batch; ++b) {
+    const int64_t P = p->prompt_len[b], T = p->draft_len[b], K = p->num_segments[b],
+                  S = p->segment_len[b];
+    if (P < 0 || T < 1 || S < 1) return PV_ERR_SHAPE;
+    const int64_t n = P + T + K * S;
+    if (n > (1 << 24)) return PV_ERR_SHAPE;
+    int64_t prev = 0;
+    for (int64_t k = 0; k < K; ++k) {
+      const int64_t pk = p->boundaries[seg + k];
+      if (pk < prev || pk > T) return PV_ERR_BOUNDARY;
+      prev = pk;
+    }
+    seg += K;
+    t->tokens += n;
+    t->max_len = n > t->max_len ? n : t->max_len;
+    t->q_tiles += (n + kTileM - 1) / kTileM;
+    t->padded_keys += align_up(n, kTileN);
+    t->mask_bytes += n * n;
+  }
+  t->segments = nseg;
+  if (t->tokens > (1ll << 27) || t->padded_keys > (1ll << 27)) return PV_ERR_SHAPE;
+  return PV_OK;
+}
+
+static pv_status validate_heads(int hq, int hkv, int d, int in_dtype) {
+  if (in_dtype != PV_BF16 && in_dtype != PV_F32) return PV_ERR_DTYPE;
+  if (hq < 1 || hkv < 1 || hq % hkv != 0 || hq / hkv > 8 || hq > 1024) return PV_ERR_SHAPE;
+  if (d != 64 && d != 128) return PV_ERR_SHAPE;
+  return PV_OK;
+}
+
+static void fill_sizes(const pv_problem* p, const Totals& t, int hq, int hkv, int d, int in_dtype,
+                       pv_sizes* s) {
+  std::memset(s, 0, sizeof(*s));
+  s->batch = p->batch;
+  s->total_tokens = t.tokens;
+  s->total_segments = t.segments;
+  s->max_seq_len = t.max_len;
+  s->n_q_tiles = t.q_tiles;
+  s->padded_keys = t.padded_keys;
+  PlanHeader h;
+  plan_layout(p->batch, t.tokens, t.segments, t.q_tiles, t.padded_keys, &h);
+  s->plan_bytes = (int64_t)h.total_ints * 4;
+  s->dense_mask_bytes = t.mask_bytes;
+  s->attn_workspace_bytes = attn_workspace_layout(t.tokens, t.padded_keys, hkv, d, in_dtype).total;
+  s->n_q_heads = hq;
+  s->n_kv_heads = hkv;
+  s->head_dim = d;
+  s->in_dtype = in_dtype;
+  s->tile_m = kTileM;
+  s->tile_n = kTileN;
+}
+
+// A pv_sizes is trusted only if it is self-consistent with the layout functions.
+static pv_status check_sizes(const pv_sizes* s, PlanHeader* h) {
+  if (!s) return PV_ERR_NULL;
+  if (s->batch < 1 || s->total_tokens < 1 || s->total_segments < 0 || s->n_q_tiles < 1 ||
+      s->tile_m != kTileM || s->tile_n != kTileN || s->padded_keys < s->total_tokens)
+    return PV_ERR_SHAPE;
+  if (validate_heads(s->n_q_heads, s->n_kv_heads, s->head_dim, s->in_dtype) != PV_OK)
+    return PV_ERR_SHAPE;
+  plan_layout((int)s->batch, s->total_tokens, s->total_segments, s->n_q_tiles, s->padded_keys, h);
+  if (s->plan_bytes != (int64_t)h->total_ints * 4) return PV_ERR_SHAPE;
+  return PV_OK;
+}
+
+static inline bool misaligned(const void* p) { return ((uintptr_t)p & 15u) != 0; }
+
+static pv_status check_arch() {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return hip_fail(e);
+  hipDeviceProp_t prop;
+  e = hipGetDeviceProperties(&prop, dev);
+  if (e != hipSuccess) return hip_fail(e);
+  if (std::strncmp(prop.gcnArchName, "gfx950", 6) != 0) return PV_ERR_ARCH;
+  return PV_OK;
+}
+
+static pv_status arch_ok_cached() {
+  static thread_local int cached_dev = -1;
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return hip_fail(e);
+  if (dev == cached_dev) return PV_OK;
+  pv_status st = check_arch();
+  if (st == PV_OK) cached_dev = dev;
+  return st;
+}
+
+}  // namespace pv
+
+using namespace pv;
+
+extern "C" {
+
+pv_status pv_query_sizes(const pv_problem* problem, int32_t n_q_heads, int32_t n_kv_heads,
+                         int32_t head_dim, int32_t in_dtype, pv_sizes* out) {
+  if (!out) return PV_ERR_NULL;
+  Totals t;
+  pv_status st = validate_problem(problem, &t);
+  if (st != PV_OK) return st;
+  st = validate_heads(n_q_heads, n_kv_heads, head_dim, in_dtype);
+  if (st != PV_OK) return st;
+  fill_sizes(problem, t, n_q_heads, n_kv_heads, head_dim, in_dtype, out);
+  return PV_OK;
+}
+
+pv_status pv_build_mask(const pv_problem* problem, const pv_sizes* sizes, void* plan_dev,
+                        int64_t plan_bytes, uint8_t* dense_mask_dev, int64_t dense_mask_bytes,
+                        void* stream) {
+  Totals t;
+  pv_status st = validate_problem(problem, &t);
+  if (st != PV_OK) return st;
+  PlanHeader h;
+  st = check_sizes(sizes, &h);
+  if (st != PV_OK) return st;
+  if (sizes->batch != problem->batch || sizes->total_tokens != t.tokens ||
+      sizes->total_segments != t.segments || sizes->n_q_tiles != t.q_tiles ||
+      sizes->padded_keys != t.padded_keys || sizes->dense_mask_bytes != t.mask_bytes)
+    return PV_ERR_SHAPE;
+  if (!plan_dev) return PV_ERR_NULL;
+  if (plan_bytes < sizes->plan_bytes) return PV_ERR_WORKSPACE;
+  if (dense_mask_dev && dense_mask_bytes < sizes->dense_mask_bytes) return PV_ERR_WORKSPACE;
+  if (misaligned(plan_dev)) return PV_ERR_ALIGN;
+
+  // Host image of the uploaded part of the plan: header, per-request arrays, boundaries.
+  std::vector<int32_t> img((size_t)h.off_device_begin, 0);
+  std::memcpy(img.data(), &h, sizeof(h));
+  const int B = problem->batch;
+  int64_t tok = 0, seg = 0, qt = 0, kp = 0, mk = 0;
+  int64_t* mask_start = reinterpret_cast<int64_t*>(img.data() + h.off_mask_start);
+  for (int b = 0; b <= B; ++b) {
+    img[h.off_tok_start + b] = (int32_t)tok;
+    img[h.off_seg_start + b] = (int32_t)seg;
+    img[h.off_qtile_start + b] = (int32_t)qt;
+    img[h.off_kpad_start + b] = (int32_t)kp;
+    mask_start[b] = mk;
+    if (b == B) break;
+    const int64_t P = problem->prompt_len[b], T = problem->draft_len[b],
+                  K = problem->num_segments[b], S = problem->segment_len[b];
+    const int64_t n = P + T + K * S;
+    img[h.off_prompt + b] = (int32_t)P;
+    img[h.off_draft + b] = (int32_t)T;
+    img[h.off_nseg + b] = (int32_t)K;
+    img[h.off_seglen + b] = (int32_t)S;
+    for (int64_t k = 0; k < K; ++k) img[h.off_bounds + seg + k] = problem->boundaries[seg + k];
+    tok += n;
+    seg += K;
+    qt += (n + kTileM - 1) / kTileM;
+    kp += align_up(n, kTileN);
+    mk += n * n;
+  }
+
+  st = arch_ok_cached();
+  if (st != PV_OK) return st;
+  hipStream_t s = (hipStream_t)stream;
+  hipError_t e = launch_upload((int32_t*)plan_dev, img.data(), (int)img.size(), s);
+  if (e != hipSuccess) return hip_fail(e);
+  e = launch_plan_kernels((int32_t*)plan_dev, h, dense_mask_dev, s);
+  if (e != hipSuccess) return hip_fail(e);
+  return PV_OK;
+}
+
+pv_status pv_masked_attention(const pv_sizes* sizes, const void* plan_dev, const void* q,
+                              const void* k, const void* v, void* out, float* lse,
+                              int32_t out_dtype, float softmax_scale, float rope_theta,
+                              void* workspace, int64_t workspace_bytes, void* stream) {
+  PlanHeader h;
+  pv_status st = check_sizes(sizes, &h);
+  if (st != PV_OK) return st;
+  if (!plan_dev || !q || !k || !v || !out || !workspace) return PV_ERR_NULL;
+  if (out_dtype != PV_BF16 && out_dtype != PV_F32) return PV_ERR_DTYPE;
+  if (sizes->in_dtype == PV_F32 && out_dtype != PV_F32) return PV_ERR_DTYPE;
+  if (!(softmax_scale >= 0.0f) || !std::isfinite(softmax_scale)) return PV_ERR_SHAPE;
+  if (!(rope_theta >= 0.0f) || !std::isfinite(rope_theta)) return PV_ERR_SHAPE;
+  const int hq = sizes->n_q_heads, hkv = sizes->n_kv_heads, d = sizes->head_dim;
+  const AttnWorkspace wl =
+      attn_workspace_layout(sizes->total_tokens, sizes->padded_keys, hkv, d, sizes->in_dtype);
+  if (workspace_bytes < wl.total) return PV_ERR_WORKSPACE;
+  if (misaligned(plan_dev) || misaligned(q) || misaligned(k) || misaligned(v) ||
+      misaligned(out) || misaligned(workspace) || ((uintptr_t)lse & 3u))
+    return PV_ERR_ALIGN;
+  st = arch_ok_cached();
+  if (st != PV_OK) return st;
+
+  const float scale = softmax_scale == 0.0f ? (float)(1.0 / std::sqrt((double)d)) : softmax_scale;
+  RopeFreq freq;
+  const bool rope = rope_theta > 0.0f;
+  for (int c = 0; c < 64; ++c)
+    freq.inv_freq[c] =
+        (rope && c < d / 2) ? std::pow((double)rope_theta, -2.0 * (double)c / (double)d) : 0.0;
+
+  hipStream_t s = (hipStream_t)stream;
+  hipError_t e;
+  if (sizes->in_dtype == PV_F32) {
+    e = launch_attn_f32((const int32_t*)plan_dev, h, (const float*)q, (const float*)k,
+                        (const float*)v, (float*)out, lse, hq, hkv, d, scale, freq, rope,
+                        (char*)workspace, wl, s);
+  } else {
+    hipEvent_t ev0 = nullptr, ev1 = nullptr;
+    if (g_profile) {
+      if (!g_ev0) {
+        e = hipEventCreate(&g_ev0);
+        if (e != hipSuccess) return hip_fail(e);
+        e = hipEventCreate(&g_ev1);
+        if (e != hipSuccess) return hip_fail(e);
+      }
+      ev0 = g_ev0;
+      ev1 = g_ev1;
+    }
+    e = launch_attn_bf16((const int32_t*)plan_dev, h, q, k, v, out, lse, hq, hkv, d, out_dtype,
+                         scale, freq, rope, (char*)workspace, wl, ev0, ev1, s);
+    if (e == hipSuccess && g_profile) g_ev_recorded = true;
+  }
+  if (e != hipSuccess) return hip_fail(e);
+  return PV_OK;
+}
+
+pv_status pv_first_reject(const pv_sizes* sizes, const void* plan_dev, const float* logits_dev,
+                          double margin_threshold, int32_t mode, int32_t* out_dev, void* stream) {
+  PlanHeader h;
+  pv_status st = check_sizes(sizes, &h);
+  if (st != PV_OK) return st;
+  if (!plan_dev || !out_dev) return PV_ERR_NULL;
+  if (sizes->total_segments > 0 && !logits_dev) return PV_ERR_NULL;
+  if (mode != 0 && mode != 1) return PV_ERR_SHAPE;
+  if (std::isnan(margin_threshold)) return PV_ERR_SHAPE;
+  if (misaligned(plan_dev) || ((uintptr_t)logits_dev & 7u) || ((uintptr_t)out_dev & 15u))
+    return PV_ERR_ALIGN;
+  st = arch_ok_cached();
+  if (st != PV_OK) return st;
+  hipError_t e = launch_first_reject((const int32_t*)plan_dev, h, logits_dev, margin_threshold,
+                                     mode, out_dev, (hipStream_t)stream);
+  if (e != hipSuccess) return hip_fail(e);
+  return PV_OK;
+}
+
+pv_status pv_plan_export(const pv_sizes* sizes, const void* plan_dev, int32_t* positions_dev,
+                         int32_t* a_end_dev, int32_t* b_start_dev, int32_t* judge_row_dev,
+                         void* stream) {
+  PlanHeader h;
+  pv_status st = check_sizes(sizes, &h);
+  if (st != PV_OK) return st;
+  if (!plan_dev) return PV_ERR_NULL;
+  st = arch_ok_cached();
+  if (st != PV_OK) return st;
+  hipError_t e = launch_plan_export((const int32_t*)plan_dev, h, positions_dev, a_end_dev,
+                                    b_start_dev, judge_row_dev, (hipStream_t)stream);
+  if (e != hipSuccess) return hip_fail(e);
+  return PV_OK;
+}
+
+pv_status pv_profile_enable(int32_t on) {
+  g_profile = on != 0;
+  if (!g_profile) g_ev_recorded = false;
+  return PV_OK;
+}
+
+pv_status pv_profile_read(float* main_kernel_ms) {
+  if (!main_kernel_ms) return PV_ERR_NULL;
+  if (!g_profile || !g_ev_recorded) return PV_ERR_SHAPE;
+  hipError_t e = hipEventSynchronize(g_ev1);
+  if (e != hipSuccess) return hip_fail(e);
+  e = hipEventElapsedTime(main_kernel_ms, g_ev0, g_ev1);
+  if (e != hipSuccess) return hip_fail(e);
+  return PV_OK;
+}
+
+const char* pv_strerror(pv_status status) {
+  switch (status) {
+    case PV_OK: return "ok";
+    case PV_ERR_NULL: return "required pointer is NULL";
+    case PV_ERR_SHAPE: return "unsupported or inconsistent shape";
+    case PV_ERR_BOUNDARY: return "boundaries must be non-decreasing and within [0, draft_len]";
+    case PV_ERR_WORKSPACE: return "buffer smaller than pv_query_sizes reported";
+    case PV_ERR_ALIGN: return "device pointer not sufficiently aligned";
+    case PV_ERR_DTYPE: return "unsupported dtype combination";
+    case PV_ERR_ARCH: return "current device is not gfx950";
+    case PV_ERR_HIP: return "HIP runtime error (see pv_last_hip_error)";
+    default: return "unknown status";
+  }
+}
+
+int32_t pv_last_hip_error(void) { return g_last_hip; }
+
+const char* pv_version(void) { return "pv 0.1 (gfx950)"; }
+
+}  // extern "C"

@@ -1,0 +1,85 @@
+// Internal declarations shared by the library's translation units (not part of the C ABI).
+#ifndef PV_INTERNAL_H_
+#define PV_INTERNAL_H_
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "pv.h"
+
+namespace pv {
+
+// Query tokens per work item and keys per tile of the MFMA path.  The plan's tile ranges are
+// expressed in these units.
+constexpr int kTileM = 32;
+constexpr int kTileN = 64;
+
+constexpr int32_t kPlanMagic = 0x50565031;  // "PVP1"
+
+// Header at the start of the plan blob.  All offsets are in int32 units from the blob start, so
+// the blob can be copied anywhere.  The header, the per-request arrays and the boundaries are
+// computed on the host and uploaded; everything after `off_device_begin` is written by kernels.
+struct PlanHeader {
+  int32_t magic, batch, total_tokens, total_segments;
+  int32_t n_q_tiles, tile_m, tile_n, padded_keys;
+  int32_t off_prompt, off_draft, off_nseg, off_seglen;   // [B] each
+  int32_t off_tok_start, off_seg_start;                  // [B+1] each
+  int32_t off_qtile_start, off_kpad_start;               // [B+1] each
+  int32_t off_mask_start;                                // int64 [B+1] (8-byte aligned)
+  int32_t off_bounds;                                    // [total_segments]
+  int32_t off_device_begin;
+  int32_t off_pos, off_aend, off_bstart;                 // [total_tokens] each
+  int32_t off_judge;                                     // [total_segments]
+  int32_t off_tiles, off_work;                           // [n_q_tiles][8] each
+  int32_t total_ints;
+  int32_t pad[6];
+};
+static_assert(sizeof(PlanHeader) == 32 * 4, "PlanHeader must be 32 ints");
+
+// One query tile of the work list (8 ints).
+struct QTile {
+  int32_t tok_base;    // first packed row of the request
+  int32_t t0;          // first local token of the tile
+  int32_t rows;        // valid tokens in the tile (1..tile_m)
+  int32_t n_full;      // key tiles [0, n_full) are visible to every row: no mask code
+  int32_t n_a;         // key tiles [n_full, n_a) need the row predicate
+  int32_t jb0, jb1;    // second range of key tiles [jb0, jb1), all with the row predicate
+  int32_t kpad_base;   // first padded key row of the request in the rotated-K / V^T workspace
+};
+
+struct RopeFreq { double inv_freq[64]; };   // theta^(-2c/D), c < D/2 <= 64
+
+// Workspace of the attention call (byte offsets), derived from pv_sizes.
+struct AttnWorkspace {
+  int64_t off_cs;      // float2 [total_tokens][D/2] (cos, sin)
+  int64_t off_krot;    // bf16 path: [Hkv][padded_keys][D] bf16; fp32 path: [total_tokens][Hkv][D] float
+  int64_t off_vt;      // bf16 path: V^T slabs, [Hkv][padded_keys/16][2][D][8] bf16
+  int64_t total;
+};
+AttnWorkspace attn_workspace_layout(int64_t total_tokens, int64_t padded_keys, int hkv, int d,
+                                    int in_dtype);
+
+// --- launchers (each returns the hipError_t of its launches) ---
+hipError_t launch_upload(int32_t* plan_dev, const int32_t* host_ints, int n, hipStream_t s);
+hipError_t launch_plan_kernels(int32_t* plan_dev, const PlanHeader& h, uint8_t* dense_mask,
+                               hipStream_t s);
+hipError_t launch_plan_export(const int32_t* plan_dev, const PlanHeader& h, int32_t* pos,
+                              int32_t* aend, int32_t* bstart, int32_t* judge, hipStream_t s);
+hipError_t launch_first_reject(const int32_t* plan_dev, const PlanHeader& h, const float* logits,
+                               double thr, int mode, int32_t* out, hipStream_t s);
+hipError_t launch_attn_f32(const int32_t* plan_dev, const PlanHeader& h, const float* q,
+                           const float* k, const float* v, float* out, float* lse, int hq,
+                           int hkv, int d, float scale, const RopeFreq& freq, bool rope,
+                           char* ws, const AttnWorkspace& wl, hipStream_t s);
+hipError_t launch_attn_bf16(const int32_t* plan_dev, const PlanHeader& h, const void* q,
+                            const void* k, const void* v, void* out, float* lse, int hq, int hkv,
+                            int d, int out_dtype, float scale, const RopeFreq& freq, bool rope,
+                            char* ws, const AttnWorkspace& wl, hipEvent_t ev0, hipEvent_t ev1,
+                            hipStream_t s);
+
+// Host-side layout of the plan; shared by pv_query_sizes and pv_build_mask.
+void plan_layout(int batch, int64_t total_tokens, int64_t total_segments, int64_t n_q_tiles,
+                 int64_t padded_keys, PlanHeader* h);
+
+}  // namespace pv
+#endif

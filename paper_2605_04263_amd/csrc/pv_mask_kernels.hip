@@ -1,0 +1,244 @@
+// Integer kernels: plan construction (row descriptors, positions, judge rows, tile work list),
+// the optional dense mask, plan export and the readout.
+#include "pv_internal.h"
+
+namespace pv {
+
+// ---------------------------------------------------------------- upload of the host image
+constexpr int kUploadInts = 896;   // 3584 bytes of kernel arguments per launch
+struct UploadChunk { int32_t v[kUploadInts]; };
+
+__global__ __launch_bounds__(256) void k_upload(int32_t* dst, UploadChunk c, int n) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) dst[i] = c.v[i];
+}
+
+hipError_t launch_upload(int32_t* plan_dev, const int32_t* host_ints, int n, hipStream_t s) {
+  // The image travels in kernel arguments: they are captured at launch, so the host buffer can
+  // be released immediately and no pageable-memory copy semantics are involved.
+  for (int o = 0; o < n; o += kUploadInts) {
+    UploadChunk c;
+    const int m = (n - o) < kUploadInts ? (n - o) : kUploadInts;
+    for (int i = 0; i < m; ++i) c.v[i] = host_ints[o + i];
+    for (int i = m; i < kUploadInts; ++i) c.v[i] = 0;
+    k_upload<<<dim3((m + 255) / 256), dim3(256), 0, s>>>(plan_dev + o, c, m);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+  return hipSuccess;
+}
+
+// ---------------------------------------------------------------- row descriptors
+struct Req {
+  int P, T, K, S, N;
+  const int32_t* bounds;
+};
+
+__device__ inline Req load_req(const int32_t* plan, const PlanHeader& h, int b) {
+  Req r;
+  r.P = plan[h.off_prompt + b];
+  r.T = plan[h.off_draft + b];
+  r.K = plan[h.off_nseg + b];
+  r.S = plan[h.off_seglen + b];
+  r.N = r.P + r.T + r.K * r.S;
+  r.bounds = plan + h.off_bounds + plan[h.off_seg_start + b];
+  return r;
+}
+
+// Visible keys of local row i are [0, a_end) and [b_start, i].  Prompt and draft rows are plain
+// causal (a_end = b_start = 0).  A row of segment k sees the prompt and the first p_k draft
+// tokens (a_end = P + p_k) and its own segment up to itself (b_start = first row of the
+// segment); its rotary position continues from the end of that prefix.
+__device__ inline void row_desc(const Req& r, int i, int* pos, int* a_end, int* b_start) {
+  const int c = r.P + r.T;
+  if (i < c) {
+    *pos = i; *a_end = 0; *b_start = 0;
+  } else {
+    const int k = (i - c) / r.S;
+    const int a = (i - c) - k * r.S;
+    *a_end = r.P + r.bounds[k];
+    *b_start = c + k * r.S;
+    *pos = *a_end + a;
+  }
+}
+
+// Largest b with start[b] <= x, for a non-decreasing start[0..n] with start[0] = 0 <= x < start[n].
+__device__ inline int find_owner(const int32_t* start, int n, int x) {
+  int lo = 0, hi = n;            // invariant: start[lo] <= x < start[hi]
+  while (hi - lo > 1) {
+    const int mid = (lo + hi) >> 1;
+    if (start[mid] <= x) lo = mid; else hi = mid;
+  }
+  // skip empty owners (start[lo] == start[lo+1]) cannot happen for lo returned here because
+  // start[lo] <= x < start[lo+1] after the loop.
+  return lo;
+}
+
+__global__ __launch_bounds__(256) void k_plan_tokens(int32_t* plan, PlanHeader h) {
+  const int g = blockIdx.x * blockDim.x + threadIdx.x;
+  if (g < h.total_tokens) {
+    const int b = find_owner(plan + h.off_tok_start, h.batch, g);
+    const Req r = load_req(plan, h, b);
+    int pos, ae, bs;
+    row_desc(r, g - plan[h.off_tok_start + b], &pos, &ae, &bs);
+    plan[h.off_pos + g] = pos;
+    plan[h.off_aend + g] = ae;
+    plan[h.off_bstart + g] = bs;
+  }
+  if (g < h.total_segments) {
+    const int b = find_owner(plan + h.off_seg_start, h.batch, g);
+    const Req r = load_req(plan, h, b);
+    const int k = g - plan[h.off_seg_start + b];
+    // the verdict of segment k is read at its last token
+    plan[h.off_judge + g] = plan[h.off_tok_start + b] + r.P + r.T + (k + 1) * r.S - 1;
+  }
+}
+
+// One thread per query tile: the union of its rows' visible key sets, in key-tile units.
+__global__ __launch_bounds__(256) void k_plan_tiles(int32_t* plan, PlanHeader h) {
+  const int t = blockIdx.x * blockDim.x + threadIdx.x;
+  if (t >= h.n_q_tiles) return;
+  const int b = find_owner(plan + h.off_qtile_start, h.batch, t);
+  const Req r = load_req(plan, h, b);
+  const int t0 = (t - plan[h.off_qtile_start + b]) * h.tile_m;
+  const int rows = min(h.tile_m, r.N - t0);
+  const int bn = h.tile_n;
+  int min_prefix = 0x7fffffff;   // min over rows of the length of the fully visible key prefix
+  int max_low = 0;               // max over rows of the end of the low range
+  int min_b = 0x7fffffff, max_i = -1;
+  for (int rr = 0; rr < rows; ++rr) {
+    const int i = t0 + rr;
+    int pos, ae, bs;
+    row_desc(r, i, &pos, &ae, &bs);
+    const bool causal = (i < r.P + r.T);
+    const int low_end = causal ? i + 1 : ae;
+    min_prefix = min(min_prefix, low_end);
+    max_low = max(max_low, low_end);
+    if (!causal) { min_b = min(min_b, bs); max_i = max(max_i, i); }
+  }
+  QTile q;
+  q.tok_base = plan[h.off_tok_start + b];
+  q.t0 = t0;
+  q.rows = rows;
+  q.n_full = min_prefix / bn;
+  q.n_a = (max_low + bn - 1) / bn;
+  if (max_i >= 0) {
+    q.jb0 = max(q.n_a, min_b / bn);
+    q.jb1 = max(q.jb0, max_i / bn + 1);
+  } else {
+    q.jb0 = q.n_a; q.jb1 = q.n_a;
+  }
+  q.kpad_base = plan[h.off_kpad_start + b];
+  reinterpret_cast<QTile*>(plan + h.off_tiles)[t] = q;
+}
+
+// Longest-first order (stable): rank = number of tiles that must run before this one.
+__global__ __launch_bounds__(256) void k_plan_sort(int32_t* plan, PlanHeader h) {
+  const int t = blockIdx.x * blockDim.x + threadIdx.x;
+  const QTile* tiles = reinterpret_cast<const QTile*>(plan + h.off_tiles);
+  __shared__ int cost_s[256];
+  QTile mine;
+  int my_cost = 0, rank = 0;
+  if (t < h.n_q_tiles) {
+    mine = tiles[t];
+    my_cost = mine.n_a + (mine.jb1 - mine.jb0);
+  }
+  for (int base = 0; base < h.n_q_tiles; base += 256) {
+    const int u = base + threadIdx.x;
+    __syncthreads();
+    cost_s[threadIdx.x] = (u < h.n_q_tiles) ? tiles[u].n_a + (tiles[u].jb1 - tiles[u].jb0) : -1;
+    __syncthreads();
+    const int m = min(256, h.n_q_tiles - base);
+    for (int x = 0; x < m; ++x) {
+      const int c = cost_s[x];
+      rank += (c > my_cost) || (c == my_cost && base + x < t);
+    }
+  }
+  if (t < h.n_q_tiles) reinterpret_cast<QTile*>(plan + h.off_work)[rank] = mine;
+}
+
+// Dense mask from the stored row descriptors (what the attention kernels consume).
+__global__ __launch_bounds__(256) void k_dense_mask(const int32_t* plan, PlanHeader h, uint8_t* mask) {
+  const int g = blockIdx.x;      // packed row
+  const int b = find_owner(plan + h.off_tok_start, h.batch, g);
+  const int base = plan[h.off_tok_start + b];
+  const int n = plan[h.off_tok_start + b + 1] - base;
+  const int i = g - base;
+  const int ae = plan[h.off_aend + g], bs = plan[h.off_bstart + g];
+  const int64_t* mask_start = reinterpret_cast<const int64_t*>(plan + h.off_mask_start);
+  uint8_t* row = mask + mask_start[b] + (int64_t)i * n;
+  for (int j = threadIdx.x; j < n; j += blockDim.x)
+    row[j] = (j < ae) || (j >= bs && j <= i) ? 1 : 0;
+}
+
+hipError_t launch_plan_kernels(int32_t* plan_dev, const PlanHeader& h, uint8_t* dense_mask,
+                               hipStream_t s) {
+  const int n1 = h.total_tokens > h.total_segments ? h.total_tokens : h.total_segments;
+  k_plan_tokens<<<dim3((n1 + 255) / 256), dim3(256), 0, s>>>(plan_dev, h);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  const int nt = (h.n_q_tiles + 255) / 256;
+  k_plan_tiles<<<dim3(nt), dim3(256), 0, s>>>(plan_dev, h);
+  e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  k_plan_sort<<<dim3(nt), dim3(256), 0, s>>>(plan_dev, h);
+  e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  if (dense_mask) {
+    k_dense_mask<<<dim3(h.total_tokens), dim3(256), 0, s>>>(plan_dev, h, dense_mask);
+    e = hipGetLastError();
+  }
+  return e;
+}
+
+// ---------------------------------------------------------------- export
+__global__ __launch_bounds__(256) void k_export(const int32_t* plan, PlanHeader h, int32_t* pos,
+                                                int32_t* aend, int32_t* bstart, int32_t* judge) {
+  const int g = blockIdx.x * blockDim.x + threadIdx.x;
+  if (g < h.total_tokens) {
+    if (pos) pos[g] = plan[h.off_pos + g];
+    if (aend) aend[g] = plan[h.off_aend + g];
+    if (bstart) bstart[g] = plan[h.off_bstart + g];
+  }
+  if (judge && g < h.total_segments) judge[g] = plan[h.off_judge + g];
+}
+
+hipError_t launch_plan_export(const int32_t* plan_dev, const PlanHeader& h, int32_t* pos,
+                              int32_t* aend, int32_t* bstart, int32_t* judge, hipStream_t s) {
+  const int n1 = h.total_tokens > h.total_segments ? h.total_tokens : h.total_segments;
+  k_export<<<dim3((n1 + 255) / 256), dim3(256), 0, s>>>(plan_dev, h, pos, aend, bstart, judge);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------- readout
+// One thread per request.  A verdict is Correct iff the fp64 margin l_C - l_I is non-negative
+// (ties count as Correct) and reaches the threshold.
+__global__ __launch_bounds__(64) void k_first_reject(const int32_t* plan, PlanHeader h,
+                                                     const float* logits, double thr, int mode,
+                                                     int32_t* out) {
+  const int b = blockIdx.x * blockDim.x + threadIdx.x;
+  if (b >= h.batch) return;
+  const int s0 = plan[h.off_seg_start + b];
+  const int K = plan[h.off_nseg + b];
+  const int32_t* bounds = plan + h.off_bounds + s0;
+  int first = K, last_ok = -1, bad = 0;
+  for (int k = 0; k < K; ++k) {
+    const double d = (double)logits[2 * (s0 + k)] - (double)logits[2 * (s0 + k) + 1];
+    const bool ok = (d >= 0.0) && (d >= thr);
+    if (ok) last_ok = k;
+    else { bad++; if (first == K) first = k; }
+  }
+  const int k_star = (mode == 0) ? first - 1 : last_ok;
+  out[4 * b + 0] = first;
+  out[4 * b + 1] = k_star;
+  out[4 * b + 2] = k_star >= 0 ? bounds[k_star] : 0;
+  out[4 * b + 3] = bad;
+}
+
+hipError_t launch_first_reject(const int32_t* plan_dev, const PlanHeader& h, const float* logits,
+                               double thr, int mode, int32_t* out, hipStream_t s) {
+  k_first_reject<<<dim3((h.batch + 63) / 64), dim3(64), 0, s>>>(plan_dev, h, logits, thr, mode, out);
+  return hipGetLastError();
+}
+
+}  // namespace pv

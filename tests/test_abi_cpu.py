@@ -1,0 +1,132 @@
+"""CPU-only checks of the C ABI: the library loads, exports every symbol the header declares,
+and rejects bad arguments on the host before anything is launched (no GPU needed)."""
+import ctypes as C
+import re
+from pathlib import Path
+
+import pytest
+
+ROOT = Path(__file__).resolve().parent.parent
+pv = pytest.importorskip("paper_2605_04263_amd.binding")
+
+
+def declared_functions():
+    text = (ROOT / "include" / "pv.h").read_text()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(pv_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported():
+    names = declared_functions()
+    assert {"pv_build_mask", "pv_masked_attention", "pv_first_reject", "pv_query_sizes"} <= set(names)
+    raw = C.CDLL(pv.LIB_PATH)
+    for n in names:
+        assert hasattr(raw, n), n
+    assert pv.lib.pv_version().decode().startswith("pv ")
+    assert pv.lib.pv_strerror(pv.PV_ERR_BOUNDARY).decode() != pv.lib.pv_strerror(pv.PV_OK).decode()
+
+
+def q(problem, hq=8, hkv=2, d=128, dt=pv.PV_BF16):
+    out = pv.PvSizes()
+    st = pv.lib.pv_query_sizes(C.byref(problem.struct), hq, hkv, d, dt, C.byref(out))
+    return st, out
+
+
+def test_query_sizes_values():
+    p = pv.make_problem([512], [2048], [16], [32], list(range(100, 1700, 100)))
+    st, s = q(p, 32, 8, 128)
+    assert st == pv.PV_OK
+    assert s.total_tokens == 512 + 2048 + 16 * 32 == 3072       # T + n*|suffix| (+ prompt)
+    assert s.total_segments == 16 and s.batch == 1 and s.max_seq_len == 3072
+    assert s.n_q_tiles == 3072 // s.tile_m
+    assert s.padded_keys == 3072
+    assert s.dense_mask_bytes == 3072 * 3072
+    assert s.plan_bytes > 4 * 3 * 3072 and s.plan_bytes % 16 == 0
+    assert s.attn_workspace_bytes >= 2 * 8 * 3072 * 128 * 2
+    # ragged: per-request rounding
+    p = pv.make_problem([3, 0], [30, 70], [2, 0], [5, 1], [4, 30])
+    st, s = q(p)
+    assert st == pv.PV_OK
+    assert s.total_tokens == 43 + 70 and s.max_seq_len == 70
+    assert s.n_q_tiles == -(-43 // s.tile_m) + -(-70 // s.tile_m)
+    assert s.padded_keys == 64 + 128
+    assert s.dense_mask_bytes == 43 * 43 + 70 * 70
+
+
+@pytest.mark.parametrize("args,expect", [
+    (dict(hq=8, hkv=3), pv.PV_ERR_SHAPE),         # Hq % Hkv != 0
+    (dict(hq=18, hkv=2), pv.PV_ERR_SHAPE),        # group of 9 > 8
+    (dict(d=96), pv.PV_ERR_SHAPE),                # unsupported head_dim
+    (dict(dt=7), pv.PV_ERR_DTYPE),
+])
+def test_head_validation(args, expect):
+    p = pv.make_problem([4], [16], [2], [3], [5, 9])
+    assert q(p, **args)[0] == expect
+
+
+@pytest.mark.parametrize("fields,expect", [
+    (([4], [16], [2], [3], [9, 5]), pv.PV_ERR_BOUNDARY),      # decreasing
+    (([4], [16], [2], [3], [5, 17]), pv.PV_ERR_BOUNDARY),     # beyond the draft
+    (([4], [16], [2], [3], [-1, 5]), pv.PV_ERR_BOUNDARY),
+    (([4], [0], [0], [1], []), pv.PV_ERR_SHAPE),              # empty draft
+    (([-1], [16], [0], [1], []), pv.PV_ERR_SHAPE),
+    (([4], [16], [-2], [1], []), pv.PV_ERR_SHAPE),
+    (([4], [16], [1], [0], [3]), pv.PV_ERR_SHAPE),            # empty segments
+])
+def test_problem_validation(fields, expect):
+    assert q(pv.make_problem(*fields))[0] == expect
+
+
+def test_boundaries_restart_per_request_and_duplicates_allowed():
+    # second request's first boundary may be smaller than the first request's last one
+    assert q(pv.make_problem([4, 4], [16, 16], [2, 2], [3, 3], [5, 9, 0, 0]))[0] == pv.PV_OK
+    assert q(pv.make_problem([0], [16], [3], [1], [16, 16, 16]))[0] == pv.PV_OK
+
+
+def test_null_pointers():
+    out = pv.PvSizes()
+    assert pv.lib.pv_query_sizes(None, 8, 2, 128, 0, C.byref(out)) == pv.PV_ERR_NULL
+    p = pv.make_problem([4], [16], [2], [3], [5, 9])
+    assert pv.lib.pv_query_sizes(C.byref(p.struct), 8, 2, 128, 0, None) == pv.PV_ERR_NULL
+    broken = pv.PvProblem(1, None, None, None, None, None)
+    assert pv.lib.pv_query_sizes(C.byref(broken), 8, 2, 128, 0, C.byref(out)) == pv.PV_ERR_NULL
+
+
+def test_launch_calls_reject_bad_arguments_before_touching_the_gpu():
+    p = pv.make_problem([4], [16], [2], [3], [5, 9])
+    st, s = q(p, 8, 2, 128)
+    assert st == pv.PV_OK
+    fake = 0x1000                              # never dereferenced on these paths
+    L = pv.lib
+    assert L.pv_build_mask(C.byref(p.struct), C.byref(s), None, s.plan_bytes, None, 0, None) == pv.PV_ERR_NULL
+    assert L.pv_build_mask(C.byref(p.struct), C.byref(s), fake, s.plan_bytes - 4, None, 0, None) == pv.PV_ERR_WORKSPACE
+    assert L.pv_build_mask(C.byref(p.struct), C.byref(s), fake, s.plan_bytes, fake, 10, None) == pv.PV_ERR_WORKSPACE
+    assert L.pv_build_mask(C.byref(p.struct), C.byref(s), fake + 4, s.plan_bytes, None, 0, None) == pv.PV_ERR_ALIGN
+    other = pv.make_problem([4], [17], [2], [3], [5, 9])
+    assert L.pv_build_mask(C.byref(other.struct), C.byref(s), fake, s.plan_bytes, None, 0, None) == pv.PV_ERR_SHAPE
+    bad = pv.make_problem([4], [16], [2], [3], [9, 5])
+    assert L.pv_build_mask(C.byref(bad.struct), C.byref(s), fake, s.plan_bytes, None, 0, None) == pv.PV_ERR_BOUNDARY
+
+    att = lambda **kw: L.pv_masked_attention(
+        C.byref(kw.get("s", s)), kw.get("plan", fake), kw.get("q", fake), fake, fake, kw.get("out", fake),
+        None, kw.get("odt", pv.PV_BF16), kw.get("scale", 0.0), kw.get("theta", 0.0), kw.get("ws", fake),
+        kw.get("wsb", s.attn_workspace_bytes), None)
+    assert att(q=None) == pv.PV_ERR_NULL
+    assert att(ws=None) == pv.PV_ERR_NULL
+    assert att(wsb=s.attn_workspace_bytes - 1) == pv.PV_ERR_WORKSPACE
+    assert att(out=fake + 2) == pv.PV_ERR_ALIGN
+    assert att(odt=3) == pv.PV_ERR_DTYPE
+    assert att(scale=-1.0) == pv.PV_ERR_SHAPE
+    assert att(theta=float("nan")) == pv.PV_ERR_SHAPE
+    tampered = pv.PvSizes.from_buffer_copy(s)
+    tampered.plan_bytes += 16
+    assert att(s=tampered) == pv.PV_ERR_SHAPE
+    st, s32 = q(p, 8, 2, 128, pv.PV_F32)
+    assert att(s=s32, odt=pv.PV_BF16, wsb=s32.attn_workspace_bytes) == pv.PV_ERR_DTYPE   # fp32 in needs fp32 out
+
+    assert L.pv_first_reject(C.byref(s), fake, None, 0.0, 0, fake, None) == pv.PV_ERR_NULL
+    assert L.pv_first_reject(C.byref(s), fake, fake, 0.0, 2, fake, None) == pv.PV_ERR_SHAPE
+    assert L.pv_first_reject(C.byref(s), fake, fake, float("nan"), 0, fake, None) == pv.PV_ERR_SHAPE
+    assert L.pv_first_reject(C.byref(s), None, fake, 0.0, 0, fake, None) == pv.PV_ERR_NULL
+    assert L.pv_plan_export(C.byref(s), None, None, None, None, None, None) == pv.PV_ERR_NULL
+    assert L.pv_profile_read(None) == pv.PV_ERR_NULL

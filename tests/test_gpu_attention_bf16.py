@@ -1,0 +1,162 @@
+"""GPU parity of the bf16 MFMA path of pv_masked_attention against the fp64 oracle.
+
+Tolerance (bf16 inputs): max-abs <= 1e-2 and mean-abs <= 1e-3 against the un-rounded oracle for
+the fp32-output run (the kernel's own arithmetic); the bf16-output run must equal that result
+rounded to nearest even, which adds at most half a bf16 ulp of the value.
+Small cases compare every element; the large named configs compare oracle-computed sampled rows
+(every row is independent given K/V, so a subset is exact)."""
+import numpy as np
+import pytest
+import torch
+
+import pv_workloads as wl
+from tests import gpu_common as gc
+
+pytestmark = pytest.mark.gpu
+pv = pytest.importorskip("paper_2605_04263_amd.binding")
+
+MAX_ABS, MEAN_ABS = 1e-2, 1e-3
+
+
+def bf16_half_ulp(x):
+    """Half the spacing of bf16 (8 significant bits) at magnitude |x|."""
+    ax = np.maximum(np.abs(x), 2.0 ** -126)
+    return 2.0 ** (np.floor(np.log2(ax)) - 8)
+
+
+def assert_bf16_is_rounded_fp32(out_bf16, out_f32):
+    """The bf16-output run must be the fp32-output run rounded to nearest even, bit for bit
+    (same kernel, same accumulation order, only the final conversion differs)."""
+    assert torch.equal(out_f32.to(torch.bfloat16).view(torch.int16), out_bf16.view(torch.int16))
+
+
+def check_errors(got, ref, bf16_out, max_abs=MAX_ABS):
+    assert np.isfinite(got).all()
+    err = np.abs(got - ref)
+    assert err.mean() <= MEAN_ABS, err.mean()
+    if bf16_out:
+        # storing the result in bf16 adds up to half a bf16 ulp of the value itself
+        assert (err <= max_abs + bf16_half_ulp(ref)).all(), err.max()
+    else:
+        assert err.max() <= max_abs, err.max()
+    return err.max(), err.mean()
+
+
+def edge_max_abs(w):
+    """Bound for the synthetic edge shapes, which are dominated by rows with a handful of keys.
+    bf16 operands give every softmax weight a relative error of up to about 2^-8 (rounding of the
+    probabilities, and of the rotated Q/K through the scores); the output moves by that times the
+    spread of the V rows it mixes, at most 2 max|V|.  The stated 1e-2 is kept as the floor and is
+    what the five named configs are held to."""
+    return max(MAX_ABS, 2.0 ** -8 * float(w.v.float().abs().max()))
+
+
+def check_full(w, max_abs=MAX_ABS):
+    """Every element: fp32 output within the stated tolerance; bf16 output = RNE of it."""
+    ver = gc.make_verifier(pv, w)
+    ver.build_mask()
+    out32, lse = gc.run_gpu_attention(pv, w, out_dtype=torch.float32, lse=True, ver=ver)
+    out16 = gc.run_gpu_attention(pv, w, out_dtype=torch.bfloat16, ver=ver)
+    ref, ref_lse = gc.oracle_attention(w, return_lse=True)
+    res = check_errors(out32.double().cpu().numpy(), ref, bf16_out=False, max_abs=max_abs)
+    assert_bf16_is_rounded_fp32(out16, out32)
+    check_errors(out16.double().cpu().numpy(), ref, bf16_out=True, max_abs=max_abs)
+    lerr = np.abs(lse.double().cpu().numpy().T - ref_lse)
+    assert lerr.max() <= 2e-2, lerr.max()
+    return res
+
+
+def check_sampled(w, n_random=128):
+    """Oracle-computed sampled rows of a large config, both output dtypes."""
+    pr = w.problem
+    ver = gc.make_verifier(pv, w)
+    ver.build_mask()
+    out32 = gc.run_gpu_attention(pv, w, out_dtype=torch.float32, ver=ver)
+    out16 = gc.run_gpu_attention(pv, w, out_dtype=torch.bfloat16, ver=ver)
+    assert bool(torch.isfinite(out32).all())
+    assert_bf16_is_rounded_fp32(out16, out32)
+    rows = gc.sample_rows(pr, n_random=n_random, seed=w.seed)
+    ref = gc.oracle_attention(w, rows_per_request=rows)
+    idx = torch.from_numpy(gc.packed_row_index(pr, rows)).to(out32.device)
+    res = check_errors(out32.index_select(0, idx).double().cpu().numpy(), ref, bf16_out=False)
+    check_errors(out16.index_select(0, idx).double().cpu().numpy(), ref, bf16_out=True)
+    return res
+
+
+EDGE = [
+    # (problem, Hq, Hkv, D, theta)
+    (wl.Problem([0], [1], [0], [1], [[]]), 4, 1, 128, 5e5),
+    (wl.Problem([0], [7], [3], [1], [[0, 0, 7]]), 4, 2, 128, 5e5),
+    (wl.Problem([5], [64], [4], [5], [[1, 33, 64, 64]]), 8, 2, 128, 5e5),
+    (wl.Problem([31], [97], [2], [33], [[50, 97]]), 5, 1, 128, 0.0),
+    (wl.Problem([3, 0, 7, 64], [20, 9, 33, 64], [3, 2, 0, 2], [5, 1, 4, 32],
+                [[0, 7, 20], [4, 4], [], [32, 64]]), 16, 2, 128, 1e4),
+    (wl.Problem([100], [300], [1], [70], [[300]]), 6, 2, 64, 5e5),
+    (wl.Problem([17], [200], [6], [16], [[0, 10, 64, 65, 128, 200]]), 3, 1, 64, 1e4),
+    (wl.Problem([64], [448], [8], [32], [[32, 64, 100, 128, 200, 300, 447, 448]]), 2, 2, 128, 5e5),
+    (wl.Problem([40], [300], [5], [24], [[17, 90, 91, 200, 300]]), 7, 1, 128, 5e5),
+]
+
+
+@pytest.mark.parametrize("idx", range(len(EDGE)))
+def test_edge_cases(idx):
+    pr, hq, hkv, d, theta = EDGE[idx]
+    w = wl.make_custom(pr, hq, hkv, d, dtype=torch.bfloat16, rope_theta=theta, seed=100 + idx)
+    check_full(w, max_abs=edge_max_abs(w))
+
+
+def test_tiny_shape_in_bf16():
+    t = wl.make("tiny", rope_theta=5e5)
+    w = wl.make_custom(t.problem, 1, 1, 64, dtype=torch.bfloat16, rope_theta=5e5, seed=7)
+    check_full(w)
+
+
+def test_8b_full():
+    check_full(wl.make("8b"))
+
+
+def test_14b_sampled():
+    check_sampled(wl.make("14b"))
+
+
+def test_ragged_sampled():
+    check_sampled(wl.make("ragged"), n_random=48)
+
+
+def test_70b_sampled():
+    check_sampled(wl.make("70b"), n_random=64)
+
+
+def test_segment_isolation_and_determinism():
+    w = wl.make("8b")
+    pr = w.problem
+    P, T, S = pr.prompt_len[0], pr.draft_len[0], pr.segment_len[0]
+    base = gc.run_gpu_attention(pv, w)
+    again = gc.run_gpu_attention(pv, w)
+    assert torch.equal(base.view(torch.int16), again.view(torch.int16))          # bit-reproducible
+    # perturb every other segment and the draft beyond segment 5's boundary: segment 5 unchanged
+    k2, v2 = w.k.clone(), w.v.clone()
+    kk = 5
+    seg = slice(P + T + kk * S, P + T + (kk + 1) * S)
+    for other in range(pr.num_segments[0]):
+        if other != kk:
+            sl = slice(P + T + other * S, P + T + (other + 1) * S)
+            k2[sl] = -k2[sl]; v2[sl] = v2[sl] + 3
+    k2[P + pr.boundaries[0][kk]:P + T] *= 2; v2[P + pr.boundaries[0][kk]:P + T] -= 5
+    w2 = wl.Workload(**{**w.__dict__, "k": k2, "v": v2})
+    pert = gc.run_gpu_attention(pv, w2)
+    assert torch.equal(base[seg].view(torch.int16), pert[seg].view(torch.int16))
+    assert not torch.equal(base[P + T - 1].view(torch.int16), pert[P + T - 1].view(torch.int16))
+
+
+def test_k0_is_plain_causal_matches_library():
+    # K = 0: the pass is the full-draft verification, a textbook causal attention
+    pr = wl.Problem([128], [384], [0], [1], [[]])
+    w = wl.make_custom(pr, 8, 2, 128, dtype=torch.bfloat16, rope_theta=0.0, seed=9)
+    out = gc.run_gpu_attention(pv, w, out_dtype=torch.float32)
+    q = w.q.float().cuda().permute(1, 0, 2).unsqueeze(0)
+    k = w.k.float().cuda().repeat_interleave(4, dim=1).permute(1, 0, 2).unsqueeze(0)
+    v = w.v.float().cuda().repeat_interleave(4, dim=1).permute(1, 0, 2).unsqueeze(0)
+    ref = torch.nn.functional.scaled_dot_product_attention(q, k, v, is_causal=True)[0].permute(1, 0, 2)
+    err = (out - ref).abs()
+    assert err.max().item() <= MAX_ABS and err.mean().item() <= MEAN_ABS

@@ -1,0 +1,114 @@
+"""GPU parity (bit-exact): pv_build_mask's dense mask, positions, judge rows and
+pv_first_reject against the oracle, through the C ABI."""
+import itertools
+
+import numpy as np
+import pytest
+import torch
+
+import pv_workloads as wl
+from oracle import pv_oracle as orc
+from tests import gpu_common as gc
+
+pytestmark = pytest.mark.gpu
+pv = pytest.importorskip("paper_2605_04263_amd.binding")
+
+EDGE_PROBLEMS = [
+    wl.Problem([0], [1], [0], [1], [[]]),                                  # smallest: one token
+    wl.Problem([0], [7], [3], [1], [[0, 0, 7]]),                           # no prompt, p=0, duplicate
+    wl.Problem([5], [64], [4], [5], [[1, 33, 64, 64]]),                    # S=5 like a chat suffix
+    wl.Problem([31], [97], [2], [33], [[50, 97]]),                         # ragged vs 32/64 tiles
+    wl.Problem([3, 0, 7, 64], [20, 9, 33, 64], [3, 2, 0, 2], [5, 1, 4, 32],
+               [[0, 7, 20], [4, 4], [], [32, 64]]),                        # ragged batch with K=0
+    wl.Problem([100], [300], [1], [70], [[300]]),                          # K=1, p=T: plain causal
+]
+
+
+def check_plan(pr, hq=4, hkv=2, d=64, dtype=torch.float32):
+    w = wl.make_custom(pr, hq, hkv, d, dtype=dtype, seed=1)
+    ver = gc.make_verifier(pv, w, dense_mask=True)
+    ver.build_mask()
+    pos, ae, bs, jr = pv.pv_plan_export(ver.sizes, ver.plan)
+    torch.cuda.synchronize()
+    assert ver.sizes.total_tokens == pr.total_tokens
+    assert np.array_equal(ver.dense_mask.cpu().numpy(), gc.oracle_dense_mask_flat(pr))
+    opos, ojr = gc.oracle_plan_arrays(pr)
+    assert np.array_equal(pos.cpu().numpy().astype(np.int64), opos)
+    assert np.array_equal(jr.cpu().numpy().astype(np.int64), ojr)
+    return ver
+
+
+@pytest.mark.parametrize("idx", range(len(EDGE_PROBLEMS)))
+def test_mask_edge_cases(idx):
+    check_plan(EDGE_PROBLEMS[idx])
+
+
+@pytest.mark.parametrize("name", ["tiny", "8b", "14b"])
+def test_mask_named_configs(name):
+    w = wl.make(name)
+    check_plan(w.problem, w.n_q_heads, w.n_kv_heads, w.head_dim, w.dtype)
+
+
+def test_mask_ragged_config_rows_sampled():
+    # full dense mask of the ragged batch is ~250 MB: compare it whole on the GPU side per request
+    w = wl.make("ragged")
+    pr = w.problem
+    ver = gc.make_verifier(pv, w, dense_mask=True)
+    ver.build_mask()
+    torch.cuda.synchronize()
+    off = 0
+    for b in range(pr.batch):
+        n = pr.seq_len(b)
+        got = ver.dense_mask[off:off + n * n].cpu().numpy().reshape(n, n)
+        exp = orc.dense_mask(pr.prompt_len[b], pr.draft_len[b], pr.segment_len[b], pr.boundaries[b])
+        assert np.array_equal(got, exp), b
+        off += n * n
+
+
+def test_readout_named_and_patterns():
+    for name in ("tiny", "8b", "ragged", "14b"):
+        w = wl.make(name)
+        pr = w.problem
+        ver = gc.make_verifier(pv, w)
+        ver.build_mask()
+        lg = w.logits.to(ver.device)
+        for tau in (0.5, 0.88, 0.985, 0.998):
+            thr = orc.margin_threshold(tau)
+            for mode in (0, 1):
+                got = ver.first_reject(lg, thr, mode).cpu().numpy()
+                exp = orc.first_reject(w.logits.numpy(), pr.num_segments, pr.boundaries, thr, mode)
+                assert np.array_equal(got, exp), (name, tau, mode)
+
+
+def test_readout_all_patterns_k6_batched():
+    K = 6
+    pats = list(itertools.product([0, 1], repeat=K))
+    B = len(pats)
+    bounds = [[2, 5, 5, 9, 14, 20]] * B
+    pr = wl.Problem([3] * B, [20] * B, [K] * B, [2] * B, bounds)
+    w = wl.make_custom(pr, 1, 1, 64, dtype=torch.float32, seed=2)
+    rng = np.random.default_rng(0)
+    lg = np.zeros((B * K, 2), np.float32)
+    for b, p in enumerate(pats):
+        for k, c in enumerate(p):
+            m = rng.uniform(2.0, 6.0) if c else rng.uniform(-6.0, 1.9)
+            base = rng.normal()
+            lg[b * K + k] = (base + m, base)
+    ver = gc.make_verifier(pv, w)
+    ver.build_mask()
+    for mode in (0, 1):
+        got = ver.first_reject(torch.from_numpy(lg).to(ver.device), 2.0, mode).cpu().numpy()
+        exp = orc.first_reject(lg, pr.num_segments, pr.boundaries, 2.0, mode)
+        assert np.array_equal(got, exp)
+
+
+def test_readout_ties_and_k0():
+    pr = wl.Problem([2, 2], [8, 8], [3, 0], [1, 1], [[1, 4, 8], []])
+    w = wl.make_custom(pr, 1, 1, 64, dtype=torch.float32, seed=3)
+    lg = np.array([[1.5, 1.5], [0.25, 0.25], [0.0, 1e-30]], np.float32)
+    ver = gc.make_verifier(pv, w)
+    ver.build_mask()
+    got = ver.first_reject(torch.from_numpy(lg).to(ver.device), 0.0, 0).cpu().numpy()
+    exp = orc.first_reject(lg, pr.num_segments, pr.boundaries, 0.0, 0)
+    assert np.array_equal(got, exp)
+    assert got[1].tolist() == [0, -1, 0, 0]
