@@ -1,0 +1,191 @@
+"""Benchmark of the parallel-prefix-verification hot path on one MI355X.
+
+A step is one pass of the whole path over one synthetic batch already resident in HBM:
+pv_build_mask -> pv_masked_attention (bf16 MFMA) -> pv_first_reject, one transformer layer.
+Prints ONE JSON line.  `value` is effective (unmasked-pair) attention FLOPs per second of the
+whole step; `roofline` prices the main attention kernel alone against the bf16 MFMA peak, its
+duration measured with HIP events on the launch stream; `cpu_baseline` times the fp64 oracle
+on the host cores of the same box.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 8b|ragged|14b|70b|tiny]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+MFMA_BF16_PEAK_TFLOPS = 2500.0      # MI355X dense bf16 MFMA peak
+
+# HBM bytes per launch of the main kernel measured with rocprofv3 --pmc (FETCH_SIZE, then
+# WRITE_SIZE), see profiles/; None where not measured.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def unmasked_pairs(problem) -> int:
+    """(query, key) pairs one head evaluates under the prefix mask."""
+    total = 0
+    for b in range(problem.batch):
+        P, T, S = problem.prompt_len[b], problem.draft_len[b], problem.segment_len[b]
+        c = P + T
+        total += c * (c + 1) // 2
+        for p in problem.boundaries[b]:
+            total += S * (P + p) + S * (S + 1) // 2
+    return total
+
+
+def ensure_built() -> None:
+    lib = os.path.join(ROOT, "paper_2605_04263_amd", "libpv.so")
+    if not os.path.exists(lib):
+        from paper_2605_04263_amd.build import build_library
+        build_library(verbose=False)
+
+
+def cpu_baseline(w, eff_flops: float) -> dict:
+    """The oracle as it stands, timed on this machine's host cores."""
+    import numpy as np
+    from oracle import pv_oracle as orc
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = os.cpu_count() or 1
+    pr = w.problem
+    q, k, v = w.q.double().numpy(), w.k.double().numpy(), w.v.double().numpy()
+    full_pairs = unmasked_pairs(pr)
+    # bounded sample: the whole workload if its dense fp64 work is small, else sampled rows
+    dense = sum(pr.seq_len(b) ** 2 for b in range(pr.batch)) * w.n_q_heads * w.head_dim * 4
+    if dense <= 4e11:
+        rows, sample = None, "whole workload (every row, every head)"
+        pairs = full_pairs
+    else:
+        rng = np.random.default_rng(0)
+        budget = 2e11
+        per_row = dense / pr.total_tokens
+        n_rows = max(8, int(budget / per_row / pr.batch))
+        rows = [sorted(set(int(x) for x in rng.integers(0, pr.seq_len(b), size=n_rows)))
+                for b in range(pr.batch)]
+        sample = f"{sum(len(r) for r in rows)} seeded random query rows (all heads) of {pr.total_tokens}"
+        pairs = 0
+        for b in range(pr.batch):
+            M = orc.dense_mask(pr.prompt_len[b], pr.draft_len[b], pr.segment_len[b], pr.boundaries[b], rows[b])
+            pairs += int(M.sum(dtype=np.int64))
+    t0 = time.perf_counter()
+    orc.masked_attention(pr.prompt_len, pr.draft_len, pr.num_segments, pr.segment_len, pr.boundaries,
+                         q, k, v, rope_theta=w.rope_theta, rows_per_request=rows)
+    orc.first_reject(w.logits.numpy(), pr.num_segments, pr.boundaries, orc.margin_threshold(w.tau), 0)
+    dt = time.perf_counter() - t0
+    flops = 4.0 * w.head_dim * w.n_q_heads * pairs
+    return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": int(threads), "kind": "oracle",
+            "sample": sample, "seconds": dt,
+            "prefixes_per_s": pr.total_segments * (pairs / full_pairs) / dt}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="8b")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1",
+              file=sys.stderr)
+        return 2
+
+    ensure_built()
+    import torch
+    import pv_workloads as wl
+    from paper_2605_04263_amd import binding as pv
+
+    if not torch.cuda.is_available():
+        print("bench.py: needs a GPU", file=sys.stderr)
+        return 2
+    dev = torch.device("cuda:0")
+    w = wl.make(args.workload)
+    pr = w.problem
+    if w.dtype != torch.bfloat16:
+        w = wl.make_custom(pr, w.n_q_heads, w.n_kv_heads, w.head_dim, torch.bfloat16, w.rope_theta, w.seed)
+    ver = pv.Verifier(pr.prompt_len, pr.draft_len, pr.num_segments, pr.segment_len, pr.flat_boundaries(),
+                      w.n_q_heads, w.n_kv_heads, w.head_dim, torch.bfloat16)
+    q, k, v, logits = w.q.to(dev), w.k.to(dev), w.v.to(dev), w.logits.to(dev)
+    out = torch.empty_like(q)
+    thr = pv.margin_from_tau(w.tau)
+
+    def step():
+        ver.build_mask()
+        ver.attention(q, k, v, out=out, rope_theta=w.rope_theta)
+        ver.first_reject(logits, thr, 0)
+
+    pairs = unmasked_pairs(pr)
+    eff_flops = 4.0 * w.head_dim * w.n_q_heads * pairs
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+
+    # per-call breakdown with events on the launch stream (untimed extra passes)
+    def timed(fn, n=50):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(n):
+            fn()
+        e1.record()
+        e1.synchronize()
+        return e0.elapsed_time(e1) / n
+    n_b = max(5, min(50, args.steps))
+    t_build = timed(ver.build_mask, n_b)
+    t_attn = timed(lambda: ver.attention(q, k, v, out=out, rope_theta=w.rope_theta), n_b)
+    t_read = timed(lambda: ver.first_reject(logits, thr, 0), n_b)
+
+    # main kernel alone: HIP events recorded by the library around its launch
+    pv.pv_profile_enable(True)
+    ks = []
+    for _ in range(n_b):
+        ver.attention(q, k, v, out=out, rope_theta=w.rope_theta)
+        ks.append(pv.pv_profile_read())
+    pv.pv_profile_enable(False)
+    kernel_ms = sum(ks) / len(ks)
+
+    achieved = eff_flops / (kernel_ms * 1e-3) / 1e12
+    traffic = MEASURED_TRAFFIC_BYTES.get(w.name)
+    line = {
+        "metric": "effective masked-attn TFLOP/s (unmasked FLOPs only), whole step: mask plan + attention + readout",
+        "value": eff_flops / (ms_per_step * 1e-3) / 1e12,
+        "unit": "TFLOP/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": w.name, "batch": pr.batch, "n_q_heads": w.n_q_heads, "n_kv_heads": w.n_kv_heads,
+                   "head_dim": w.head_dim, "total_tokens": pr.total_tokens, "total_segments": pr.total_segments,
+                   "rope_theta": w.rope_theta, "unmasked_pairs": pairs, "effective_flops": eff_flops,
+                   "layers": 1},
+        "pct_bf16_mfma_peak_step": 100.0 * eff_flops / (ms_per_step * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+        "verified_prefixes_per_s": pr.total_segments / (ms_per_step * 1e-3),
+        "breakdown_ms": {"pv_build_mask": t_build, "pv_masked_attention": t_attn, "pv_first_reject": t_read,
+                         "attention_main_kernel": kernel_ms},
+        "attn_tflops": eff_flops / (t_attn * 1e-3) / 1e12,
+        "roofline": {"bound": "mfma", "kernel": "k_attn_bf16", "achieved": achieved,
+                     "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": traffic},
+    }
+    if not args.no_cpu_baseline:
+        line["cpu_baseline"] = cpu_baseline(w, eff_flops)
+    print(json.dumps(line))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -139,7 +139,6 @@ __global__ __launch_bounds__(G * 64, 2) void k_attn_bf16(
   constexpr int KT = D / 16;            // MFMA steps along the feature dim for S^T
   constexpr int DB = D / 32;            // 32-feature blocks of O^T
   constexpr int CH = 64 * D / 8;        // 16-byte chunks per K (or V^T) tile
-  constexpr int PER = (CH + NT - 1) / NT;
   constexpr int CPR = D / 8;            // chunks per key row
   __shared__ uint4 sK[2][CH];
   __shared__ uint4 sV[2][CH];
@@ -196,26 +195,22 @@ __global__ __launch_bounds__(G * 64, 2) void k_attn_bf16(
   // ---- key tile sequence: [0, n_a) then [jb0, jb1)
   const int n_tiles = tile.n_a + (tile.jb1 - tile.jb0);
   const int64_t head_base = ((int64_t)kvh * h.padded_keys + tile.kpad_base) * D;   // elements
-  uint4 pk[PER], pv[PER];
   auto tile_index = [&](int idx) { return idx < tile.n_a ? idx : tile.jb0 + (idx - tile.n_a); };
-  auto gload = [&](int jt) {
+  // Stage one K tile and one V^T tile with direct global->LDS loads: a wave instruction moves 64
+  // consecutive 16-byte chunks, lane l landing at chunk (base + l).  The K bank swizzle (chunk
+  // pos ^ row within each 256-byte row) is applied by choosing which global chunk a lane fetches.
+  auto stage = [&](int jt, int buf) {
     const uint4* gk = reinterpret_cast<const uint4*>(krot + head_base + (int64_t)jt * 64 * D);
     const uint4* gv = reinterpret_cast<const uint4*>(vt + head_base + (int64_t)jt * 64 * D);
-#pragma unroll
-    for (int n = 0; n < PER; ++n) {
-      const int L = tid + n * NT;
-      if (CH % NT == 0 || L < CH) { pk[n] = gk[L]; pv[n] = gv[L]; }
-    }
-  };
-  auto sstore = [&](int buf) {
-#pragma unroll
-    for (int n = 0; n < PER; ++n) {
-      const int L = tid + n * NT;
-      if (CH % NT == 0 || L < CH) {
-        const int R = L >> 4, pos = L & 15;
-        sK[buf][(R << 4) + (pos ^ (R & 15))] = pk[n];     // bank swizzle per 256-byte row
-        sV[buf][L] = pv[n];
-      }
+    for (int c = wave; c < CH / 64; c += G) {
+      const int P = c * 64 + lane;
+      const int R = P >> 4, pos = P & 15;
+      __builtin_amdgcn_global_load_lds(
+          (const __attribute__((address_space(1))) void*)(gk + (R << 4) + (pos ^ (R & 15))),
+          (__attribute__((address_space(3))) void*)(&sK[buf][c * 64]), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds(
+          (const __attribute__((address_space(1))) void*)(gv + P),
+          (__attribute__((address_space(3))) void*)(&sV[buf][c * 64]), 16, 0, 0);
     }
   };
 
@@ -226,15 +221,16 @@ __global__ __launch_bounds__(G * 64, 2) void k_attn_bf16(
     for (int r = 0; r < 16; ++r) o[db][r] = 0.0f;
   float m_run = -1e30f, l_run = 0.0f;
 
-  gload(tile_index(0));
-  sstore(0);
-  __syncthreads();
+  stage(tile_index(0), 0);
 
   for (int idx = 0; idx < n_tiles; ++idx) {
     const int cur = idx & 1;
     const int jt = tile_index(idx);
-    const bool more = idx + 1 < n_tiles;
-    if (more) gload(tile_index(idx + 1));
+    // tile idx has landed (own loads: vmcnt(0); other waves': barrier); the barrier also means
+    // every wave is done reading the other buffer, which the next stage() overwrites
+    __builtin_amdgcn_s_waitcnt(0x0f70);
+    __syncthreads();
+    if (idx + 1 < n_tiles) stage(tile_index(idx + 1), cur ^ 1);
 
     // ---- S^T = K Q^T for two blocks of 32 keys
     f32x16 s[2];
@@ -313,8 +309,6 @@ __global__ __launch_bounds__(G * 64, 2) void k_attn_bf16(
       }
     }
 
-    if (more) sstore(cur ^ 1);
-    __syncthreads();
   }
 
   // ---- epilogue
