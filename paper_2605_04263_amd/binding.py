@@ -15,7 +15,7 @@ from typing import Optional, Sequence
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libpv.so")
+LIB_PATH = os.environ.get("PV_LIBRARY", os.path.join(_HERE, "libpv.so"))   # override: a developer build
 
 PV_OK = 0
 PV_ERR_NULL, PV_ERR_SHAPE, PV_ERR_BOUNDARY, PV_ERR_WORKSPACE = -1, -2, -3, -4

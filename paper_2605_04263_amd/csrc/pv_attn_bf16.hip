@@ -14,6 +14,8 @@
 // of the online softmax is a per-lane scalar.  O^T = V^T P^T then takes P^T straight from the
 // accumulator registers of S^T (the key order inside a slab is chosen to make that a pure
 // register repack).
+#include <type_traits>
+
 #include "pv_internal.h"
 
 namespace pv {
@@ -44,6 +46,30 @@ __device__ __forceinline__ float pair_sum(float x) {
   auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
   return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
+
+// 16-byte LDS read issued as inline assembly: the compiler neither tracks it nor orders it against
+// the global->LDS staging loads (its own LDS reads would wait for every outstanding staging load).
+// The caller must execute LDS_WAIT on the destination registers before using them.
+template <int OFF>
+__device__ __forceinline__ bf16x8 lds_read_b128(unsigned addr) {
+  bf16x8 r;
+  asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(r) : "v"(addr), "n"(OFF));
+  return r;
+}
+// s_waitcnt lgkmcnt(n) tied to the registers it makes valid, so no consumer can be moved above it.
+#define LDS_WAIT4(n, a, b, c, d) \
+  asm volatile("s_waitcnt lgkmcnt(" #n ")" : "+v"(a), "+v"(b), "+v"(c), "+v"(d))
+
+template <int I, int N, typename F>
+__device__ __forceinline__ void static_for(F&& f) {
+  if constexpr (I < N) {
+    f(std::integral_constant<int, I>{});
+    static_for<I + 1, N>(f);
+  }
+}
+
+// s_waitcnt immediate (gfx9 encoding) that waits for vmcnt <= n only.
+__host__ __device__ constexpr int vmcnt_imm(int n) { return 0x0f70 | (n & 15) | ((n >> 4) << 14); }
 
 // ---------------------------------------------------------------- rotary table
 __global__ __launch_bounds__(256) void k_rope_table_bf16(const int32_t* plan, PlanHeader h,
@@ -129,7 +155,10 @@ __global__ __launch_bounds__(256) void k_prep_kv(const int32_t* __restrict__ pla
 }
 
 // ---------------------------------------------------------------- main kernel
-template <int D, int G>
+// FOLD: the softmax scale (times log2 e) is folded into Q before its single bf16 rounding, which
+// is free when Q is rotated anyway.  Without rotation Q enters the MFMA exactly as given and the
+// scale multiplies the fp32 score inside the exponent instead.
+template <int D, int G, bool FOLD>
 __global__ __launch_bounds__(G * 64, 2) void k_attn_bf16(
     const int32_t* __restrict__ plan, PlanHeader h, const uint16_t* __restrict__ q,
     const uint16_t* __restrict__ krot, const uint16_t* __restrict__ vt,
@@ -138,10 +167,16 @@ __global__ __launch_bounds__(G * 64, 2) void k_attn_bf16(
   constexpr int NT = G * 64;
   constexpr int KT = D / 16;            // MFMA steps along the feature dim for S^T
   constexpr int DB = D / 32;            // 32-feature blocks of O^T
-  constexpr int CH = 64 * D / 8;        // 16-byte chunks per K (or V^T) tile
+  constexpr int CH32 = 32 * D / 8;      // 16-byte chunks per 32-key K (or V^T) stage
   constexpr int CPR = D / 8;            // chunks per key row
-  __shared__ uint4 sK[2][CH];
-  __shared__ uint4 sV[2][CH];
+  constexpr int NS = (D == 128) ? 5 : 8;                 // LDS stages of 32 keys (K and V^T each)
+  constexpr int LPS = 2 * ((CH32 / 64) / G);             // staging loads every wave issues per stage
+  // One LDS array on purpose: with several LDS variables the compiler attaches alias scopes and
+  // then makes every LDS read wait for all outstanding global->LDS loads, which would serialise
+  // the staging pipeline.  Ordering is enforced here with explicit vmcnt waits and barriers.
+  __shared__ uint4 smem[NS][2][CH32];
+#define sK(buf) smem[buf][0]
+#define sV(buf) smem[buf][1]
 
   const int kvh = blockIdx.x % hkv;
   const QTile tile = reinterpret_cast<const QTile*>(plan + h.off_work)[blockIdx.x / hkv];
@@ -154,8 +189,7 @@ __global__ __launch_bounds__(G * 64, 2) void k_attn_bf16(
   int a_end = 0, b_start = 0;
   if (valid) { a_end = plan[h.off_aend + g]; b_start = plan[h.off_bstart + g]; }
 
-  // ---- Q fragments: rotate and round to bf16 once.  The softmax scale (times log2 e) is applied
-  // to the fp32 scores inside the exponent's fma, so un-rotated inputs enter the MFMA exactly.
+  // ---- Q fragments: rotate, (FOLD) multiply by softmax scale * log2(e), round to bf16 once
   bf16x8 qf[KT];
   {
     float x[KT][8];
@@ -184,33 +218,105 @@ __global__ __launch_bounds__(G * 64, 2) void k_attn_bf16(
 #pragma unroll
     for (int t = 0; t < KT; ++t) {
       uint4 pk;
-      pk.x = pack_bf16(x[t][0], x[t][1]);
-      pk.y = pack_bf16(x[t][2], x[t][3]);
-      pk.z = pack_bf16(x[t][4], x[t][5]);
-      pk.w = pack_bf16(x[t][6], x[t][7]);
+      const float f = FOLD ? qscale : 1.0f;
+      pk.x = pack_bf16(x[t][0] * f, x[t][1] * f);
+      pk.y = pack_bf16(x[t][2] * f, x[t][3] * f);
+      pk.z = pack_bf16(x[t][4] * f, x[t][5] * f);
+      pk.w = pack_bf16(x[t][6] * f, x[t][7] * f);
       qf[t] = as_bf16x8(pk);
     }
   }
 
-  // ---- key tile sequence: [0, n_a) then [jb0, jb1)
+  // ---- key steps.  A key tile of the plan (64 keys) is two steps of 32 keys; tiles run over
+  // [0, n_a) then [jb0, jb1).  Step j lives in LDS stage j % NS.
   const int n_tiles = tile.n_a + (tile.jb1 - tile.jb0);
+  const int n_steps = 2 * n_tiles;
   const int64_t head_base = ((int64_t)kvh * h.padded_keys + tile.kpad_base) * D;   // elements
-  auto tile_index = [&](int idx) { return idx < tile.n_a ? idx : tile.jb0 + (idx - tile.n_a); };
-  // Stage one K tile and one V^T tile with direct global->LDS loads: a wave instruction moves 64
-  // consecutive 16-byte chunks, lane l landing at chunk (base + l).  The K bank swizzle (chunk
-  // pos ^ row within each 256-byte row) is applied by choosing which global chunk a lane fetches.
-  auto stage = [&](int jt, int buf) {
-    const uint4* gk = reinterpret_cast<const uint4*>(krot + head_base + (int64_t)jt * 64 * D);
-    const uint4* gv = reinterpret_cast<const uint4*>(vt + head_base + (int64_t)jt * 64 * D);
-    for (int c = wave; c < CH / 64; c += G) {
-      const int P = c * 64 + lane;
-      const int R = P >> 4, pos = P & 15;
+  auto step_key0 = [&](int j) {           // first key (request-local) of step j
+    const int idx = j >> 1;
+    const int jt = idx < tile.n_a ? idx : tile.jb0 + (idx - tile.n_a);
+    return jt * 64 + (j & 1) * 32;
+  };
+  // Direct global->LDS staging: a wave instruction moves 64 consecutive 16-byte chunks, lane l
+  // landing at chunk (base + l).  The K bank swizzle (chunk pos ^ row within each 256-byte row)
+  // is applied by choosing which global chunk a lane fetches.
+  const int wave_s = __builtin_amdgcn_readfirstlane(wave);      // wave index as a scalar
+  constexpr int NREP = (CH32 / 64 + G - 1) / G;                  // staging instructions per wave
+  unsigned gk_off[NREP], gv_off[NREP];                           // per-lane byte offsets in a stage
+#pragma unroll
+  for (int n = 0; n < NREP; ++n) {
+    const int P = (wave_s + n * G) * 64 + lane;
+    const int R = P >> 4, pos = P & 15;
+    gk_off[n] = (unsigned)(((R << 4) + (pos ^ (R & 15))) * 16);
+    gv_off[n] = (unsigned)(P * 16);
+  }
+  const unsigned smem_base =
+      (unsigned)(uintptr_t)(__attribute__((address_space(3))) char*)(char*)&smem[0][0][0];
+  constexpr unsigned STAGE_BYTES = 2 * CH32 * 16;
+  const char* krot_b = reinterpret_cast<const char*>(krot) + head_base * 2;
+  const char* vt_b = reinterpret_cast<const char*>(vt) + head_base * 2;
+  // stage step j into LDS stage `buf` (scalar bases + per-lane offsets: a few scalar ops per step)
+  auto stage = [&](int j, int buf) {
+    if (j >= n_steps) return;
+    const int64_t off = (int64_t)step_key0(j) * (D * 2);
+    const char* gk = krot_b + off;
+    const char* gv = vt_b + off;
+    const unsigned lds0 = smem_base + (unsigned)buf * STAGE_BYTES;
+#pragma unroll
+    for (int n = 0; n < NREP; ++n) {
+      const int c = wave_s + n * G;
+      if ((CH32 / 64) % G != 0 && c >= CH32 / 64) break;
       __builtin_amdgcn_global_load_lds(
-          (const __attribute__((address_space(1))) void*)(gk + (R << 4) + (pos ^ (R & 15))),
-          (__attribute__((address_space(3))) void*)(&sK[buf][c * 64]), 16, 0, 0);
+          (const __attribute__((address_space(1))) void*)(gk + gk_off[n]),
+          (__attribute__((address_space(3))) void*)(uintptr_t)(lds0 + c * 1024), 16, 0, 0);
       __builtin_amdgcn_global_load_lds(
-          (const __attribute__((address_space(1))) void*)(gv + P),
-          (__attribute__((address_space(3))) void*)(&sV[buf][c * 64]), 16, 0, 0);
+          (const __attribute__((address_space(1))) void*)(gv + gv_off[n]),
+          (__attribute__((address_space(3))) void*)(uintptr_t)(lds0 + CH32 * 16 + c * 1024), 16, 0, 0);
+    }
+  };
+  bf16x8 kf[KT];          // K operand of the next S^T
+  bf16x8 vf[2][DB];       // V^T operands of the current step
+  // per-lane LDS byte offsets inside a stage (the K swizzle makes them lane dependent per k-step)
+  unsigned k_off[KT];
+#pragma unroll
+  for (int t = 0; t < KT; ++t) {
+    const int L = qrow * CPR + 2 * t + hh;
+    const int R = L >> 4, pos = L & 15;
+    k_off[t] = smem_base + (unsigned)(((R << 4) + (pos ^ (R & 15))) * 16);
+  }
+  const unsigned v_off = smem_base + (unsigned)((CH32 + hh * D + qrow) * 16);
+  auto load_k = [&](int buf) {
+    const unsigned sb = (unsigned)buf * STAGE_BYTES;
+    static_for<0, KT>([&](auto t) { kf[t] = lds_read_b128<0>(k_off[t] + sb); });
+  };
+  auto load_v = [&](int buf) {
+    const unsigned a = v_off + (unsigned)buf * STAGE_BYTES;
+    static_for<0, 2>([&](auto uu) {
+      static_for<0, DB>([&](auto db) { vf[uu][db] = lds_read_b128<(uu * 2 * D + db * 32) * 16>(a); });
+    });
+  };
+  auto wait_k = [&]() {   // K operands valid; the DB*2 newer V reads may still be in flight
+    if constexpr (D == 128) {
+      asm volatile("s_waitcnt lgkmcnt(8)" : "+v"(kf[0]), "+v"(kf[1]), "+v"(kf[2]), "+v"(kf[3]),
+                   "+v"(kf[4]), "+v"(kf[5]), "+v"(kf[6]), "+v"(kf[7]));
+    } else {
+      asm volatile("s_waitcnt lgkmcnt(4)" : "+v"(kf[0]), "+v"(kf[1]), "+v"(kf[2]), "+v"(kf[3]));
+    }
+  };
+  auto wait_k_only = [&]() {   // nothing newer in flight
+    if constexpr (D == 128) {
+      asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(kf[0]), "+v"(kf[1]), "+v"(kf[2]), "+v"(kf[3]),
+                   "+v"(kf[4]), "+v"(kf[5]), "+v"(kf[6]), "+v"(kf[7]));
+    } else {
+      asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(kf[0]), "+v"(kf[1]), "+v"(kf[2]), "+v"(kf[3]));
+    }
+  };
+  auto wait_v = [&]() {
+    if constexpr (D == 128) {
+      asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(vf[0][0]), "+v"(vf[0][1]), "+v"(vf[0][2]),
+                   "+v"(vf[0][3]), "+v"(vf[1][0]), "+v"(vf[1][1]), "+v"(vf[1][2]), "+v"(vf[1][3]));
+    } else {
+      asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(vf[0][0]), "+v"(vf[0][1]), "+v"(vf[1][0]), "+v"(vf[1][1]));
     }
   };
 
@@ -219,98 +325,132 @@ __global__ __launch_bounds__(G * 64, 2) void k_attn_bf16(
   for (int db = 0; db < DB; ++db)
 #pragma unroll
     for (int r = 0; r < 16; ++r) o[db][r] = 0.0f;
-  float m_run = -1e30f, l_run = 0.0f;
+  // Scores are accumulated on top of cinit = -mref (log2 units), so the MFMA result is already
+  // s - mref and the probability is a bare exp2.  mref is only re-centred when a row sum leaves
+  // a safe window (see the re-centre block below); l_run and o are relative to mref.
+  float mref = 0.0f, l_run = 0.0f;       // mref in score units (log2 units when FOLD)
+  const float esc = FOLD ? 1.0f : qscale;   // exponent scale: p = 2^(esc * (s - mref))
+  auto prob = [&](float x) { return __builtin_amdgcn_exp2f(FOLD ? x : x * esc); };
+  f32x16 cinit;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) cinit[r] = 0.0f;
 
-  stage(tile_index(0), 0);
+#pragma unroll
+  for (int j = 0; j < NS - 1; ++j) stage(j, j);
+  __builtin_amdgcn_s_waitcnt(0x0f70);
+  __syncthreads();
+  load_k(0);
+  wait_k_only();
+  f32x16 s_cur = cinit;
+#pragma unroll
+  for (int t = 0; t < KT; ++t) s_cur = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[t], qf[t], s_cur, 0, 0, 0);
+  __builtin_amdgcn_sched_barrier(0);
+  load_k(n_steps > 1 ? 1 : 0);
+  // LDS stage of step j (bv), of step j+2 (bk) and the stage freed by step j-1 (bs)
+  int bv = 0, bk = 2 % NS, bs = NS - 1;
 
-  for (int idx = 0; idx < n_tiles; ++idx) {
-    const int cur = idx & 1;
-    const int jt = tile_index(idx);
-    // tile idx has landed (own loads: vmcnt(0); other waves': barrier); the barrier also means
-    // every wave is done reading the other buffer, which the next stage() overwrites
-    __builtin_amdgcn_s_waitcnt(0x0f70);
+  for (int j = 0; j < n_steps; ++j) {
+    // Steps <= j+2 must have landed before this iteration's reads; stage j-1's buffer is free once
+    // every wave has passed the barrier.  Up to NS-4 newer stages may stay in flight.
+    {
+      const int newer = min(j + NS - 2, n_steps - 1) - (j + 2);
+      if (newer >= NS - 4 && NS > 4) __builtin_amdgcn_s_waitcnt(vmcnt_imm((NS - 4) * LPS));
+      else __builtin_amdgcn_s_waitcnt(0x0f70);
+    }
     __syncthreads();
-    if (idx + 1 < n_tiles) stage(tile_index(idx + 1), cur ^ 1);
+    stage(j + NS - 1, bs);
+    load_v(bv);
 
-    // ---- S^T = K Q^T for two blocks of 32 keys
-    f32x16 s[2];
+    const int key0 = step_key0(j);
+    if (key0 >= tile.n_full * 64) {               // step not fully visible: apply the row predicate
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) s[kb][r] = 0.0f;
-#pragma unroll
-    for (int t = 0; t < KT; ++t) {
-#pragma unroll
-      for (int kb = 0; kb < 2; ++kb) {
-        const int L = (kb * 32 + qrow) * CPR + 2 * t + hh;
-        const int R = L >> 4, pos = L & 15;
-        const bf16x8 a = as_bf16x8(sK[cur][(R << 4) + (pos ^ (R & 15))]);
-        s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[t], s[kb], 0, 0, 0);
+      for (int r = 0; r < 16; ++r) {
+        const int key = key0 + 8 * (r / 4) + 4 * hh + (r % 4);
+        const bool vis = (key < a_end) | ((key >= b_start) & (key <= i_loc));   // branch-free
+        s_cur[r] = vis ? s_cur[r] : -INFINITY;
       }
     }
+    wait_k();
+    __builtin_amdgcn_sched_barrier(0);
 
-    // ---- mask (only tiles that are not fully visible)
-    if (jt >= tile.n_full) {
+    // ---- S^T of step j+1 (MFMA) while the probabilities of step j are formed (VALU)
+    asm volatile("" : "+v"(cinit));
+    f32x16 s_next = cinit;
 #pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int key = jt * 64 + kb * 32 + 8 * (r / 4) + 4 * hh + (r % 4);
-          const bool vis = (key < a_end) | ((key >= b_start) & (key <= i_loc));   // branch-free
-          s[kb][r] = vis ? s[kb][r] : -INFINITY;
-        }
-    }
+    for (int t = 0; t < KT; ++t) s_next = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[t], qf[t], s_next, 0, 0, 0);
 
-    // ---- online softmax on raw scores; p = 2^(qscale * (s - m))
-    float mx = s[0][0];
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[kb][r]);
-    mx = pair_max(mx);
-    const float m_new = fmaxf(m_run, mx);
-    const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * qscale);
-    const float neg_mc = -m_new * qscale;
     // p rounded to bf16 once; the row sum is taken over the rounded values (v_dot2c with a pair
     // of ones), so that O is an exact convex combination of V rows with the weights the MFMA sees
-    uint4 pp[4];
+    unsigned pw[8];
     float rs = 0.0f;
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      unsigned w[4];
+    for (int e = 0; e < 8; ++e) {
+      pw[e] = pack_bf16(prob(s_cur[2 * e]), prob(s_cur[2 * e + 1]));
+      rs = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pw[e]),
+                                           __builtin_bit_cast(bf16x2, 0x3f803f80u), rs, false);
+    }
+    // interleave: after each MFMA of the dependent chain, a share of the softmax VALU work
 #pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const int r = 8 * (u & 1) + 2 * e;
-        const float p0 = __builtin_amdgcn_exp2f(fmaf(s[u >> 1][r], qscale, neg_mc));
-        const float p1 = __builtin_amdgcn_exp2f(fmaf(s[u >> 1][r + 1], qscale, neg_mc));
-        w[e] = pack_bf16(p0, p1);
-        rs = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, w[e]),
+    for (int t = 0; t < KT; ++t) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x002, 32 / KT + 1, 0);
+    }
+    // Re-centre when a partial row sum is outside [2^-40, 2^40] (also catches inf/NaN/0): one
+    // exact online-softmax step for the whole wave.  Rare: first steps of a row, masked steps
+    // with no visible key, or scores drifting by more than 40 octaves.  The reference moves to
+    // this step's row maximum, but never so far down that the history (l, O) would leave fp32
+    // range: delta >= log2(l) - 20.  Both half-waves of a row take identical decisions.
+    if (__builtin_amdgcn_ballot_w64(!(rs >= 0x1p-40f && rs <= 0x1p40f)) != 0) {
+      float mx = s_cur[0];
+#pragma unroll
+      for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s_cur[r]);
+      mx = pair_max(mx);
+      const float l_tot = pair_sum(l_run);
+      if (mx > -INFINITY && mx < INFINITY) {      // rows with no visible key keep their reference
+        float delta = mx, alpha = 0.0f;           // empty history: nothing to rescale
+        if (l_tot > 0.0f) {
+          delta = fmaxf(mx, (__builtin_amdgcn_logf(l_tot) - 20.0f) / esc);
+          alpha = __builtin_amdgcn_exp2f(-delta * esc);
+        }
+        mref += delta;
+        l_run *= alpha;
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) o[db][r] *= alpha;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) { s_cur[r] -= delta; s_next[r] -= delta; cinit[r] = -mref; }
+      }
+      rs = 0.0f;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        pw[e] = pack_bf16(prob(s_cur[2 * e]), prob(s_cur[2 * e + 1]));
+        rs = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pw[e]),
                                              __builtin_bit_cast(bf16x2, 0x3f803f80u), rs, false);
       }
-      pp[u] = make_uint4(w[0], w[1], w[2], w[3]);
     }
-    l_run = l_run * alpha + rs;
-    if (__any(m_new > m_run)) {
+    l_run += rs;
+
+    // ---- O^T += V^T P^T for step j, while the K operand of step j+2 is fetched from LDS
+    __builtin_amdgcn_sched_barrier(0);
+    wait_v();
+    load_k(j + 2 < n_steps ? bk : bv);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int uu = 0; uu < 2; ++uu) {
+      const bf16x8 pf = as_bf16x8(make_uint4(pw[4 * uu], pw[4 * uu + 1], pw[4 * uu + 2], pw[4 * uu + 3]));
 #pragma unroll
       for (int db = 0; db < DB; ++db)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) o[db][r] *= alpha;
+        o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[uu][db], pf, o[db], 0, 0, 0);
     }
-    m_run = m_new;
-
-    // ---- O^T += V^T P^T
-#pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      const bf16x8 pf = as_bf16x8(pp[u]);
-#pragma unroll
-      for (int db = 0; db < DB; ++db) {
-        const bf16x8 a = as_bf16x8(sV[cur][(u * 2 + hh) * D + db * 32 + qrow]);
-        o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf, o[db], 0, 0, 0);
-      }
-    }
-
+    s_cur = s_next;
+    bv = bv + 1 == NS ? 0 : bv + 1;
+    bk = bk + 1 == NS ? 0 : bk + 1;
+    bs = bs + 1 == NS ? 0 : bs + 1;
   }
 
+#undef sK
+#undef sV
   // ---- epilogue
   const float l_tot = pair_sum(l_run);
   if (valid) {
@@ -339,7 +479,7 @@ __global__ __launch_bounds__(G * 64, 2) void k_attn_bf16(
         }
     }
     if (lse && hh == 0)
-      lse[(int64_t)head * h.total_tokens + g] = (m_run * qscale + log2f(l_tot)) * 0.6931471805599453f;
+      lse[(int64_t)head * h.total_tokens + g] = (mref * esc + log2f(l_tot)) * 0.6931471805599453f;
   }
 }
 
@@ -349,8 +489,12 @@ static hipError_t launch_main(const int32_t* plan, const PlanHeader& h, const ui
                               float* lse, int hq, int hkv, float qscale, bool rope, bool out_f32,
                               hipStream_t s) {
   const dim3 grid((unsigned)((int64_t)h.n_q_tiles * hkv));
-  k_attn_bf16<D, G><<<grid, dim3(G * 64), 0, s>>>(plan, h, q, krot, vt, cs, out, lse, hq, hkv,
-                                                  qscale, rope, out_f32);
+  if (rope)
+    k_attn_bf16<D, G, true><<<grid, dim3(G * 64), 0, s>>>(plan, h, q, krot, vt, cs, out, lse, hq, hkv,
+                                                          qscale, rope, out_f32);
+  else
+    k_attn_bf16<D, G, false><<<grid, dim3(G * 64), 0, s>>>(plan, h, q, krot, vt, cs, out, lse, hq, hkv,
+                                                           qscale, rope, out_f32);
   return hipGetLastError();
 }
 
