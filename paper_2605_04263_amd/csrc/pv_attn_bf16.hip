@@ -14,62 +14,12 @@
 // of the online softmax is a per-lane scalar.  O^T = V^T P^T then takes P^T straight from the
 // accumulator registers of S^T (the key order inside a slab is chosen to make that a pure
 // register repack).
-#include <type_traits>
+#include <cstdlib>
+#include <cstring>
 
-#include "pv_internal.h"
+#include "pv_attn_common.h"
 
 namespace pv {
-
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
-typedef __attribute__((ext_vector_type(2))) float f32x2;
-typedef __attribute__((ext_vector_type(16))) float f32x16;
-
-__device__ __forceinline__ unsigned pack_bf16(float a, float b) {
-  f32x2 v = {a, b};
-  bf16x2 r = __builtin_convertvector(v, bf16x2);   // round to nearest even
-  return __builtin_bit_cast(unsigned, r);
-}
-__device__ __forceinline__ float bf16_lo(unsigned u) { return __uint_as_float(u << 16); }
-__device__ __forceinline__ float bf16_hi(unsigned u) { return __uint_as_float(u & 0xffff0000u); }
-
-__device__ __forceinline__ bf16x8 as_bf16x8(uint4 u) { return __builtin_bit_cast(bf16x8, u); }
-
-// Value held by the lane 32 away (both halves get the other's value via max/sum of the pair).
-__device__ __forceinline__ float pair_max(float x) {
-  const unsigned u = __float_as_uint(x);
-  auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
-  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
-}
-__device__ __forceinline__ float pair_sum(float x) {
-  const unsigned u = __float_as_uint(x);
-  auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
-  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
-}
-
-// 16-byte LDS read issued as inline assembly: the compiler neither tracks it nor orders it against
-// the global->LDS staging loads (its own LDS reads would wait for every outstanding staging load).
-// The caller must execute LDS_WAIT on the destination registers before using them.
-template <int OFF>
-__device__ __forceinline__ bf16x8 lds_read_b128(unsigned addr) {
-  bf16x8 r;
-  asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(r) : "v"(addr), "n"(OFF));
-  return r;
-}
-// s_waitcnt lgkmcnt(n) tied to the registers it makes valid, so no consumer can be moved above it.
-#define LDS_WAIT4(n, a, b, c, d) \
-  asm volatile("s_waitcnt lgkmcnt(" #n ")" : "+v"(a), "+v"(b), "+v"(c), "+v"(d))
-
-template <int I, int N, typename F>
-__device__ __forceinline__ void static_for(F&& f) {
-  if constexpr (I < N) {
-    f(std::integral_constant<int, I>{});
-    static_for<I + 1, N>(f);
-  }
-}
-
-// s_waitcnt immediate (gfx9 encoding) that waits for vmcnt <= n only.
-__host__ __device__ constexpr int vmcnt_imm(int n) { return 0x0f70 | (n & 15) | ((n >> 4) << 14); }
 
 // ---------------------------------------------------------------- rotary table
 __global__ __launch_bounds__(256) void k_rope_table_bf16(const int32_t* plan, PlanHeader h,
@@ -189,43 +139,7 @@ __global__ __launch_bounds__(G * 64, 2) void k_attn_bf16(
   int a_end = 0, b_start = 0;
   if (valid) { a_end = plan[h.off_aend + g]; b_start = plan[h.off_bstart + g]; }
 
-  // ---- Q fragments: rotate, (FOLD) multiply by softmax scale * log2(e), round to bf16 once
-  bf16x8 qf[KT];
-  {
-    float x[KT][8];
-    const uint16_t* qp = q + (g * hq + head) * D + 8 * hh;
-#pragma unroll
-    for (int t = 0; t < KT; ++t) {
-      uint4 raw = make_uint4(0, 0, 0, 0);
-      if (valid) raw = *reinterpret_cast<const uint4*>(qp + 16 * t);
-      const unsigned* pr = reinterpret_cast<const unsigned*>(&raw);
-#pragma unroll
-      for (int e = 0; e < 4; ++e) { x[t][2 * e] = bf16_lo(pr[e]); x[t][2 * e + 1] = bf16_hi(pr[e]); }
-    }
-    if (rope && valid) {
-      const float2* tb = cs + g * (D / 2) + 8 * hh;
-#pragma unroll
-      for (int t = 0; t < KT / 2; ++t) {
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-          const float2 cs1 = tb[16 * t + e];
-          const float lo = x[t][e], hi = x[t + KT / 2][e];
-          x[t][e] = lo * cs1.x - hi * cs1.y;
-          x[t + KT / 2][e] = hi * cs1.x + lo * cs1.y;
-        }
-      }
-    }
-#pragma unroll
-    for (int t = 0; t < KT; ++t) {
-      uint4 pk;
-      const float f = FOLD ? qscale : 1.0f;
-      pk.x = pack_bf16(x[t][0] * f, x[t][1] * f);
-      pk.y = pack_bf16(x[t][2] * f, x[t][3] * f);
-      pk.z = pack_bf16(x[t][4] * f, x[t][5] * f);
-      pk.w = pack_bf16(x[t][6] * f, x[t][7] * f);
-      qf[t] = as_bf16x8(pk);
-    }
-  }
+  bf16x8 qf[KT];          // Q operand of this wave's head (filled below, once the tile is in LDS)
 
   // ---- key steps.  A key tile of the plan (64 keys) is two steps of 32 keys; tiles run over
   // [0, n_a) then [jb0, jb1).  Step j lives in LDS stage j % NS.
@@ -295,28 +209,16 @@ __global__ __launch_bounds__(G * 64, 2) void k_attn_bf16(
       static_for<0, DB>([&](auto db) { vf[uu][db] = lds_read_b128<(uu * 2 * D + db * 32) * 16>(a); });
     });
   };
-  auto wait_k = [&]() {   // K operands valid; the DB*2 newer V reads may still be in flight
+  auto wait_kv = [&]() {   // every outstanding LDS read of this wave has landed
     if constexpr (D == 128) {
-      asm volatile("s_waitcnt lgkmcnt(8)" : "+v"(kf[0]), "+v"(kf[1]), "+v"(kf[2]), "+v"(kf[3]),
-                   "+v"(kf[4]), "+v"(kf[5]), "+v"(kf[6]), "+v"(kf[7]));
+      asm volatile("s_waitcnt lgkmcnt(0)"
+                   : "+v"(kf[0]), "+v"(kf[1]), "+v"(kf[2]), "+v"(kf[3]), "+v"(kf[4]), "+v"(kf[5]),
+                     "+v"(kf[6]), "+v"(kf[7]), "+v"(vf[0][0]), "+v"(vf[0][1]), "+v"(vf[0][2]),
+                     "+v"(vf[0][3]), "+v"(vf[1][0]), "+v"(vf[1][1]), "+v"(vf[1][2]), "+v"(vf[1][3]));
     } else {
-      asm volatile("s_waitcnt lgkmcnt(4)" : "+v"(kf[0]), "+v"(kf[1]), "+v"(kf[2]), "+v"(kf[3]));
-    }
-  };
-  auto wait_k_only = [&]() {   // nothing newer in flight
-    if constexpr (D == 128) {
-      asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(kf[0]), "+v"(kf[1]), "+v"(kf[2]), "+v"(kf[3]),
-                   "+v"(kf[4]), "+v"(kf[5]), "+v"(kf[6]), "+v"(kf[7]));
-    } else {
-      asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(kf[0]), "+v"(kf[1]), "+v"(kf[2]), "+v"(kf[3]));
-    }
-  };
-  auto wait_v = [&]() {
-    if constexpr (D == 128) {
-      asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(vf[0][0]), "+v"(vf[0][1]), "+v"(vf[0][2]),
-                   "+v"(vf[0][3]), "+v"(vf[1][0]), "+v"(vf[1][1]), "+v"(vf[1][2]), "+v"(vf[1][3]));
-    } else {
-      asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(vf[0][0]), "+v"(vf[0][1]), "+v"(vf[1][0]), "+v"(vf[1][1]));
+      asm volatile("s_waitcnt lgkmcnt(0)"
+                   : "+v"(kf[0]), "+v"(kf[1]), "+v"(kf[2]), "+v"(kf[3]), "+v"(vf[0][0]),
+                     "+v"(vf[0][1]), "+v"(vf[1][0]), "+v"(vf[1][1]));
     }
   };
 
@@ -325,149 +227,289 @@ __global__ __launch_bounds__(G * 64, 2) void k_attn_bf16(
   for (int db = 0; db < DB; ++db)
 #pragma unroll
     for (int r = 0; r < 16; ++r) o[db][r] = 0.0f;
-  // Scores are accumulated on top of cinit = -mref (log2 units), so the MFMA result is already
-  // s - mref and the probability is a bare exp2.  mref is only re-centred when a row sum leaves
-  // a safe window (see the re-centre block below); l_run and o are relative to mref.
-  float mref = 0.0f, l_run = 0.0f;       // mref in score units (log2 units when FOLD)
+  // Scores are accumulated on top of cinit = -mref, so the MFMA result is already s - mref and the
+  // probability is a bare exp2.  mref is only re-centred when a row sum leaves a safe window (see
+  // recentre below); l_run and o are relative to mref.
+  float mref = 0.0f, l_run = 0.0f;          // mref in score units (log2 units when FOLD)
   const float esc = FOLD ? 1.0f : qscale;   // exponent scale: p = 2^(esc * (s - mref))
   auto prob = [&](float x) { return __builtin_amdgcn_exp2f(FOLD ? x : x * esc); };
   f32x16 cinit;
 #pragma unroll
   for (int r = 0; r < 16; ++r) cinit[r] = 0.0f;
 
-#pragma unroll
-  for (int j = 0; j < NS - 1; ++j) stage(j, j);
-  __builtin_amdgcn_s_waitcnt(0x0f70);
-  __syncthreads();
-  load_k(0);
-  wait_k_only();
-  f32x16 s_cur = cinit;
-#pragma unroll
-  for (int t = 0; t < KT; ++t) s_cur = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[t], qf[t], s_cur, 0, 0, 0);
-  __builtin_amdgcn_sched_barrier(0);
-  load_k(n_steps > 1 ? 1 : 0);
-  // LDS stage of step j (bv), of step j+2 (bk) and the stage freed by step j-1 (bs)
-  int bv = 0, bk = 2 % NS, bs = NS - 1;
-
-  for (int j = 0; j < n_steps; ++j) {
-    // Steps <= j+2 must have landed before this iteration's reads; stage j-1's buffer is free once
-    // every wave has passed the barrier.  Up to NS-4 newer stages may stay in flight.
-    {
-      const int newer = min(j + NS - 2, n_steps - 1) - (j + 2);
-      if (newer >= NS - 4 && NS > 4) __builtin_amdgcn_s_waitcnt(vmcnt_imm((NS - 4) * LPS));
-      else __builtin_amdgcn_s_waitcnt(0x0f70);
-    }
-    __syncthreads();
-    stage(j + NS - 1, bs);
-    load_v(bv);
-
-    const int key0 = step_key0(j);
-    if (key0 >= tile.n_full * 64) {               // step not fully visible: apply the row predicate
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int key = key0 + 8 * (r / 4) + 4 * hh + (r % 4);
-        const bool vis = (key < a_end) | ((key >= b_start) & (key <= i_loc));   // branch-free
-        s_cur[r] = vis ? s_cur[r] : -INFINITY;
-      }
-    }
-    wait_k();
-    __builtin_amdgcn_sched_barrier(0);
-
-    // ---- S^T of step j+1 (MFMA) while the probabilities of step j are formed (VALU)
+  auto qk = [&]() {
     asm volatile("" : "+v"(cinit));
-    f32x16 s_next = cinit;
+    f32x16 acc = cinit;
 #pragma unroll
-    for (int t = 0; t < KT; ++t) s_next = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[t], qf[t], s_next, 0, 0, 0);
-
-    // p rounded to bf16 once; the row sum is taken over the rounded values (v_dot2c with a pair
-    // of ones), so that O is an exact convex combination of V rows with the weights the MFMA sees
-    unsigned pw[8];
+    for (int t = 0; t < KT; ++t) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[t], qf[t], acc, 0, 0, 0);
+    return acc;
+  };
+  auto apply_mask = [&](f32x16& sc, int key0) {
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int key = key0 + 8 * (r / 4) + 4 * hh + (r % 4);
+      const bool vis = (key < a_end) | ((key >= b_start) & (key <= i_loc));   // branch-free
+      sc[r] = vis ? sc[r] : -INFINITY;
+    }
+  };
+  // p rounded to bf16 once; the row sum is taken over the rounded values (v_dot2c with a pair of
+  // ones), so that O is an exact convex combination of V rows with the weights the MFMA sees
+  auto probs = [&](const f32x16& sc, unsigned (&pw)[8]) {
     float rs = 0.0f;
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
-      pw[e] = pack_bf16(prob(s_cur[2 * e]), prob(s_cur[2 * e + 1]));
+      pw[e] = pack_bf16(prob(sc[2 * e]), prob(sc[2 * e + 1]));
       rs = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pw[e]),
                                            __builtin_bit_cast(bf16x2, 0x3f803f80u), rs, false);
     }
-    // interleave: after each MFMA of the dependent chain, a share of the softmax VALU work
+    return rs;
+  };
+  auto out_of_window = [&](float rs) {
+    return __builtin_amdgcn_ballot_w64(!(rs >= 0x1p-40f && rs <= 0x1p40f)) != 0;
+  };
+  // One exact online-softmax step for the whole wave: taken when a partial row sum is outside
+  // [2^-40, 2^40] (also catches inf/NaN/0).  Rare: first steps of a row, masked steps with no
+  // visible key, or scores drifting by more than 40 octaves.  The reference moves to this step's
+  // row maximum, but never so far down that the history (l, O) would leave fp32 range:
+  // delta >= log2(l) - 20.  `sc` are the scores being exponentiated, `sn` the scores already
+  // accumulated for the following step with the old reference.  Both half-waves of a row take
+  // identical decisions.
+  auto recentre = [&](f32x16& sc, f32x16& sn, unsigned (&pw)[8]) {
+    float mx = sc[0];
 #pragma unroll
-    for (int t = 0; t < KT; ++t) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-      __builtin_amdgcn_sched_group_barrier(0x002, 32 / KT + 1, 0);
-    }
-    // Re-centre when a partial row sum is outside [2^-40, 2^40] (also catches inf/NaN/0): one
-    // exact online-softmax step for the whole wave.  Rare: first steps of a row, masked steps
-    // with no visible key, or scores drifting by more than 40 octaves.  The reference moves to
-    // this step's row maximum, but never so far down that the history (l, O) would leave fp32
-    // range: delta >= log2(l) - 20.  Both half-waves of a row take identical decisions.
-    if (__builtin_amdgcn_ballot_w64(!(rs >= 0x1p-40f && rs <= 0x1p40f)) != 0) {
-      float mx = s_cur[0];
-#pragma unroll
-      for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s_cur[r]);
-      mx = pair_max(mx);
-      const float l_tot = pair_sum(l_run);
-      if (mx > -INFINITY && mx < INFINITY) {      // rows with no visible key keep their reference
-        float delta = mx, alpha = 0.0f;           // empty history: nothing to rescale
-        if (l_tot > 0.0f) {
-          delta = fmaxf(mx, (__builtin_amdgcn_logf(l_tot) - 20.0f) / esc);
-          alpha = __builtin_amdgcn_exp2f(-delta * esc);
-        }
-        mref += delta;
-        l_run *= alpha;
-#pragma unroll
-        for (int db = 0; db < DB; ++db)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) o[db][r] *= alpha;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) { s_cur[r] -= delta; s_next[r] -= delta; cinit[r] = -mref; }
+    for (int r = 1; r < 16; ++r) mx = fmaxf(mx, sc[r]);
+    mx = pair_max(mx);
+    const float l_tot = pair_sum(l_run);
+    if (mx > -INFINITY && mx < INFINITY) {      // rows with no visible key keep their reference
+      float delta = mx, alpha = 0.0f;           // empty history: nothing to rescale
+      if (l_tot > 0.0f) {
+        delta = fmaxf(mx, (__builtin_amdgcn_logf(l_tot) - 20.0f) / esc);
+        alpha = __builtin_amdgcn_exp2f(-delta * esc);
       }
-      rs = 0.0f;
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        pw[e] = pack_bf16(prob(s_cur[2 * e]), prob(s_cur[2 * e + 1]));
-        rs = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pw[e]),
-                                             __builtin_bit_cast(bf16x2, 0x3f803f80u), rs, false);
-      }
-    }
-    l_run += rs;
-
-    // ---- O^T += V^T P^T for step j, while the K operand of step j+2 is fetched from LDS
-    __builtin_amdgcn_sched_barrier(0);
-    wait_v();
-    load_k(j + 2 < n_steps ? bk : bv);
-    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-    for (int uu = 0; uu < 2; ++uu) {
-      const bf16x8 pf = as_bf16x8(make_uint4(pw[4 * uu], pw[4 * uu + 1], pw[4 * uu + 2], pw[4 * uu + 3]));
+      mref += delta;
+      l_run *= alpha;
 #pragma unroll
       for (int db = 0; db < DB; ++db)
-        o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[uu][db], pf, o[db], 0, 0, 0);
+#pragma unroll
+        for (int r = 0; r < 16; ++r) o[db][r] *= alpha;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) { sc[r] -= delta; sn[r] -= delta; cinit[r] = -mref; }
     }
-    s_cur = s_next;
-    bv = bv + 1 == NS ? 0 : bv + 1;
-    bk = bk + 1 == NS ? 0 : bk + 1;
-    bs = bs + 1 == NS ? 0 : bs + 1;
+    return probs(sc, pw);
+  };
+
+  // ---- Q tile (and its cos/sin rows) through LDS.  A lane needs 16-byte pieces of 32 different
+  // rows, which as direct global loads is one cache line per lane; instead the waves copy whole
+  // rows with global->LDS loads (swizzled like K) into the stage memory, read their operands
+  // from there, and only then start the K/V staging.
+  {
+    constexpr int QCH = G * 32 * CPR;                 // 16-byte chunks of the Q tile
+    constexpr int CSR = D / 4;                        // chunks per table row (D/2 float2)
+    constexpr int CSCH = 32 * CSR;
+    static_assert((QCH + CSCH) * 16 <= NS * 2 * CH32 * 16, "Q tile and table must fit the stages");
+    const int rows_m1 = tile.rows - 1;
+    const int64_t tok0 = (int64_t)tile.tok_base + tile.t0;
+    const unsigned q_area = smem_base, cs_area = smem_base + QCH * 16;
+#pragma unroll
+    for (int n = 0; n < QCH / 64 / G; ++n) {          // 32*CPR/64 instructions per wave
+      const int c = wave_s + n * G;
+      const int P = c * 64 + lane;
+      const int R = P >> 4, pos = P & 15;
+      const int Pg = (R << 4) + (pos ^ (R & 15));     // global chunk that lands at LDS chunk P
+      const int row = Pg / CPR, ch = Pg % CPR;
+      const int hl = row >> 5, tok = min(row & 31, rows_m1);
+      const uint16_t* src = q + ((tok0 + tok) * hq + kvh * G + hl) * D + (ch << 3);
+      __builtin_amdgcn_global_load_lds(
+          (const __attribute__((address_space(1))) void*)src,
+          (__attribute__((address_space(3))) void*)(uintptr_t)(q_area + c * 1024), 16, 0, 0);
+    }
+    if (FOLD) {
+#pragma unroll
+      for (int n = 0; n < (CSCH / 64 + G - 1) / G; ++n) {
+        const int c = wave_s + n * G;
+        if ((CSCH / 64) % G != 0 && c >= CSCH / 64) break;
+        const int P = c * 64 + lane;
+        const int R = P >> 4, pos = P & 15;
+        const int Pg = (R << 4) + (pos ^ (R & 15));
+        const int tok = min(Pg / CSR, rows_m1), ch = Pg % CSR;
+        const float2* src = cs + (tok0 + tok) * (D / 2) + (ch << 1);
+        __builtin_amdgcn_global_load_lds(
+            (const __attribute__((address_space(1))) void*)src,
+            (__attribute__((address_space(3))) void*)(uintptr_t)(cs_area + c * 1024), 16, 0, 0);
+      }
+    }
+    __builtin_amdgcn_s_waitcnt(0x0f70);
+    __syncthreads();
+    const uint4* q_lds = &smem[0][0][0];
+    const uint4* cs_lds = q_lds + QCH;
+    auto swz = [](int L) { const int R = L >> 4, pos = L & 15; return (R << 4) + (pos ^ (R & 15)); };
+    float x[KT][8];
+#pragma unroll
+    for (int t = 0; t < KT; ++t) {
+      const uint4 raw = q_lds[swz((wave * 32 + qrow) * CPR + 2 * t + hh)];
+      const unsigned* pr = reinterpret_cast<const unsigned*>(&raw);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) { x[t][2 * e] = bf16_lo(pr[e]); x[t][2 * e + 1] = bf16_hi(pr[e]); }
+    }
+    if (FOLD) {             // FOLD <=> rotary embedding on: pair (c, c + D/2), c = 16 t + 8 hh + e
+#pragma unroll
+      for (int t = 0; t < KT / 2; ++t) {
+#pragma unroll
+        for (int k2 = 0; k2 < 4; ++k2) {
+          const uint4 w = cs_lds[swz(qrow * CSR + 8 * t + 4 * hh + k2)];
+          const float c0 = __uint_as_float(w.x), s0r = __uint_as_float(w.y);
+          const float c1 = __uint_as_float(w.z), s1r = __uint_as_float(w.w);
+          const float lo0 = x[t][2 * k2], hi0 = x[t + KT / 2][2 * k2];
+          const float lo1 = x[t][2 * k2 + 1], hi1 = x[t + KT / 2][2 * k2 + 1];
+          x[t][2 * k2] = lo0 * c0 - hi0 * s0r;
+          x[t + KT / 2][2 * k2] = hi0 * c0 + lo0 * s0r;
+          x[t][2 * k2 + 1] = lo1 * c1 - hi1 * s1r;
+          x[t + KT / 2][2 * k2 + 1] = hi1 * c1 + lo1 * s1r;
+        }
+      }
+    }
+    const float f = FOLD ? qscale : 1.0f;
+#pragma unroll
+    for (int t = 0; t < KT; ++t) {
+      uint4 pk;
+      pk.x = pack_bf16(x[t][0] * f, x[t][1] * f);
+      pk.y = pack_bf16(x[t][2] * f, x[t][3] * f);
+      pk.z = pack_bf16(x[t][4] * f, x[t][5] * f);
+      pk.w = pack_bf16(x[t][6] * f, x[t][7] * f);
+      qf[t] = as_bf16x8(pk);
+    }
+    __syncthreads();                                  // the stage memory may now be overwritten
   }
+
+  // ---- pipeline prologue: P(0), S(1), K operand of step 2, V operand of step 0
+#pragma unroll
+  for (int j = 0; j < NS; ++j) stage(j, j);
+  __builtin_amdgcn_s_waitcnt(0x0f70);
+  __syncthreads();
+  const int last = n_steps - 1;
+  load_k(0);
+  wait_kv();
+  f32x16 s0 = qk();
+  __builtin_amdgcn_sched_barrier(0);
+  load_k(min(1, last));
+  if (0 >= tile.n_full * 64) apply_mask(s0, step_key0(0));
+  unsigned p0[8];
+  float rs0 = probs(s0, p0);
+  wait_kv();
+  f32x16 s1 = qk();
+  __builtin_amdgcn_sched_barrier(0);
+  {   // same issue order as inside the loop: V^T t, K t, V^T t+1, ...
+    const unsigned sbk = (unsigned)(min(2, last) % NS) * STAGE_BYTES;
+    static_for<0, KT>([&](auto t) {
+      constexpr int uu = decltype(t)::value / DB, db = decltype(t)::value % DB;
+      vf[uu][db] = lds_read_b128<(uu * 2 * D + db * 32) * 16>(v_off);
+      kf[t] = lds_read_b128<0>(k_off[t] + sbk);
+    });
+  }
+  if (out_of_window(rs0)) rs0 = recentre(s0, s1, p0);
+  l_run += rs0;
+  // LDS stage of step j+1 (b1), of step j+3 (b3) and the stage freed by step j (bs = j % NS)
+  int b1 = min(1, last) % NS, b3 = min(3, last) % NS, bs = 0;
+
+  for (int j = 0; j < n_steps; ++j) {
+    // The operands of this iteration are in registers once the LDS reads land; after the barrier
+    // stage j % NS is free and steps <= j+3 must be visible: up to NS-4 newer stages in flight.
+    // only the last read of the previous block (a K operand) may still be outstanding: the V^T
+    // reads of step j have left the stage that is refilled after the barrier
+    asm volatile("s_waitcnt lgkmcnt(1)" ::: "memory");
+    {
+      const int newer = min(j + NS - 1, last) - (j + 3);
+      if (newer >= NS - 4 && NS > 4) __builtin_amdgcn_s_waitcnt(vmcnt_imm((NS - 4) * LPS));
+      else __builtin_amdgcn_s_waitcnt(0x0f70);
+    }
+    __builtin_amdgcn_s_barrier();
+    stage(j + NS, bs);
+    const bool have1 = j + 1 <= last;
+    if (have1) {
+      const int key0 = step_key0(j + 1);
+      if (key0 >= tile.n_full * 64) apply_mask(s1, key0);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+
+    // ---- one fused block: O^T += V^T P^T of step j and S^T of step j+2 on the MFMA pipe, the
+    // probabilities of step j+1 on the VALU, and the LDS reads of the next iteration's operands
+    // (V^T of step j+1, K of step j+3), each issued as soon as the register it refills has been
+    // consumed.  LDS reads complete in order and 2 KT are issued per iteration, so an operand read
+    // one iteration ago is valid once at most 2 KT - 1 younger reads are outstanding.
+    asm volatile("" : "+v"(cinit));
+    f32x16 s2 = cinit;
+    const bf16x8 pfa = as_bf16x8(make_uint4(p0[0], p0[1], p0[2], p0[3]));
+    const bf16x8 pfb = as_bf16x8(make_uint4(p0[4], p0[5], p0[6], p0[7]));
+    unsigned p1[8];
+    float rs1 = 0.0f;
+    const unsigned sb1 = (unsigned)b1 * STAGE_BYTES, sb3 = (unsigned)b3 * STAGE_BYTES;
+    static_for<0, KT>([&](auto t) {
+      constexpr int uu = decltype(t)::value / DB, db = decltype(t)::value % DB;
+      if constexpr (KT == 8) asm volatile("s_waitcnt lgkmcnt(15)" : "+v"(vf[uu][db]));
+      else asm volatile("s_waitcnt lgkmcnt(7)" : "+v"(vf[uu][db]));
+      o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[uu][db], uu ? pfb : pfa, o[db], 0, 0, 0);
+      vf[uu][db] = lds_read_b128<(uu * 2 * D + db * 32) * 16>(v_off + sb1);
+      if constexpr (KT == 8) asm volatile("s_waitcnt lgkmcnt(15)" : "+v"(kf[t]));
+      else asm volatile("s_waitcnt lgkmcnt(7)" : "+v"(kf[t]));
+      s2 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[t], qf[t], s2, 0, 0, 0);
+      kf[t] = lds_read_b128<0>(k_off[t] + sb3);
+      constexpr int PAIRS = 8 / KT;                   // probability pairs formed per k-step
+#pragma unroll
+      for (int e = decltype(t)::value * PAIRS; e < (decltype(t)::value + 1) * PAIRS; ++e) {
+        p1[e] = pack_bf16(prob(s1[2 * e]), prob(s1[2 * e + 1]));
+        rs1 = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, p1[e]),
+                                              __builtin_bit_cast(bf16x2, 0x3f803f80u), rs1, false);
+      }
+    });
+    __builtin_amdgcn_sched_barrier(0);
+    if (have1) {
+      if (out_of_window(rs1)) rs1 = recentre(s1, s2, p1);
+      l_run += rs1;
+    }
+    s1 = s2;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) p0[e] = p1[e];
+    bs = bs + 1 == NS ? 0 : bs + 1;
+    b1 = (j + 2 <= last) ? (b1 + 1 == NS ? 0 : b1 + 1) : b1;
+    b3 = (j + 4 <= last) ? (b3 + 1 == NS ? 0 : b3 + 1) : b3;
+  }
+  wait_kv();
 
 #undef sK
 #undef sV
-  // ---- epilogue
+  // ---- epilogue: normalise, then transpose through LDS so that every output row leaves as one
+  // contiguous run (2 D bytes in bf16; fp32 goes in two halves of D/2 features to bound the area)
   const float l_tot = pair_sum(l_run);
-  if (valid) {
+  __syncthreads();                                    // every wave is done with the stages
+  {
     const float inv = 1.0f / l_tot;
-    const int64_t row = (g * hq + head) * D;
+    const int64_t tok0 = (int64_t)tile.tok_base + tile.t0;
+    constexpr int RS = 2 * D + 16;                    // row stride: 16 B of padding spreads the banks
+    char* tr = reinterpret_cast<char*>(&smem[0][0][0]) + (size_t)wave * (32 * RS);
     if (out_f32) {
-      float* op = reinterpret_cast<float*>(out) + row;
+      float* op = reinterpret_cast<float*>(out);
 #pragma unroll
-      for (int db = 0; db < DB; ++db)
+      for (int half = 0; half < 2; ++half) {
 #pragma unroll
-        for (int gq = 0; gq < 4; ++gq) {
-          float4 w = make_float4(o[db][4 * gq] * inv, o[db][4 * gq + 1] * inv,
-                                 o[db][4 * gq + 2] * inv, o[db][4 * gq + 3] * inv);
-          *reinterpret_cast<float4*>(op + db * 32 + 8 * gq + 4 * hh) = w;
+        for (int dbh = 0; dbh < DB / 2; ++dbh)
+#pragma unroll
+          for (int gq = 0; gq < 4; ++gq) {
+            const int db = half * (DB / 2) + dbh;
+            const float4 w = make_float4(o[db][4 * gq] * inv, o[db][4 * gq + 1] * inv,
+                                         o[db][4 * gq + 2] * inv, o[db][4 * gq + 3] * inv);
+            *reinterpret_cast<float4*>(tr + qrow * RS + (dbh * 32 + 8 * gq + 4 * hh) * 4) = w;
+          }
+        constexpr int LPR = D / 8;                    // lanes per row: D/2 floats = 2 D bytes
+#pragma unroll
+        for (int it = 0; it < 32 * LPR / 64; ++it) {
+          const int row = it * (64 / LPR) + lane / LPR, c = lane % LPR;
+          const float4 w = *reinterpret_cast<const float4*>(tr + row * RS + c * 16);
+          if (row < tile.rows)
+            *reinterpret_cast<float4*>(op + ((tok0 + row) * hq + head) * D + half * (D / 2) + c * 4) = w;
         }
+      }
     } else {
-      uint16_t* op = reinterpret_cast<uint16_t*>(out) + row;
+      uint16_t* op = reinterpret_cast<uint16_t*>(out);
 #pragma unroll
       for (int db = 0; db < DB; ++db)
 #pragma unroll
@@ -475,10 +517,17 @@ __global__ __launch_bounds__(G * 64, 2) void k_attn_bf16(
           uint2 w;
           w.x = pack_bf16(o[db][4 * gq] * inv, o[db][4 * gq + 1] * inv);
           w.y = pack_bf16(o[db][4 * gq + 2] * inv, o[db][4 * gq + 3] * inv);
-          *reinterpret_cast<uint2*>(op + db * 32 + 8 * gq + 4 * hh) = w;
+          *reinterpret_cast<uint2*>(tr + qrow * RS + (db * 32 + 8 * gq + 4 * hh) * 2) = w;
         }
+      constexpr int LPR = D / 8;                      // lanes per row: 2 D bytes in 16-byte pieces
+#pragma unroll
+      for (int it = 0; it < 32 * LPR / 64; ++it) {
+        const int row = it * (64 / LPR) + lane / LPR, c = lane % LPR;
+        const uint4 w = *reinterpret_cast<const uint4*>(tr + row * RS + c * 16);
+        if (row < tile.rows) *reinterpret_cast<uint4*>(op + ((tok0 + row) * hq + head) * D + c * 8) = w;
+      }
     }
-    if (lse && hh == 0)
+    if (lse && hh == 0 && valid)
       lse[(int64_t)head * h.total_tokens + g] = (mref * esc + log2f(l_tot)) * 0.6931471805599453f;
   }
 }
@@ -539,8 +588,20 @@ hipError_t launch_attn_bf16(const int32_t* plan_dev, const PlanHeader& h, const 
   const float qscale = scale * 1.4426950408889634f;
   const bool out_f32 = out_dtype == PV_F32;
   if (ev0) { e = hipEventRecord(ev0, s); if (e != hipSuccess) return e; }
-  if (d == 64) e = dispatch_g<64>(hq / hkv, plan_dev, h, kq, krot, vt, cs, out, lse, hq, hkv, qscale, rope, out_f32, s);
-  else e = dispatch_g<128>(hq / hkv, plan_dev, h, kq, krot, vt, cs, out, lse, hq, hkv, qscale, rope, out_f32, s);
+  // Default: the generic kernel (32 query rows per wave, two workgroups per CU).  The variant with
+  // 64 query rows per wave is selected with PV_ATTN_KERNEL=m64 (A/B measurements); it halves the
+  // LDS operand traffic but runs one workgroup per CU and currently loses more to the exposed
+  // per-item prologue than it gains.
+  static const bool use_m64 = [] {
+    const char* v = std::getenv("PV_ATTN_KERNEL");
+    return v && std::strcmp(v, "m64") == 0;
+  }();
+  e = !use_m64 ? hipErrorNotSupported
+                    : launch_attn_m64(plan_dev, h, kq, krot, vt, cs, out, lse, hq, hkv, d, qscale, rope, out_f32, s);
+  if (e == hipErrorNotSupported) {
+    if (d == 64) e = dispatch_g<64>(hq / hkv, plan_dev, h, kq, krot, vt, cs, out, lse, hq, hkv, qscale, rope, out_f32, s);
+    else e = dispatch_g<128>(hq / hkv, plan_dev, h, kq, krot, vt, cs, out, lse, hq, hkv, qscale, rope, out_f32, s);
+  }
   if (e != hipSuccess) return e;
   if (ev1) { e = hipEventRecord(ev1, s); if (e != hipSuccess) return e; }
   return hipSuccess;

@@ -1,0 +1,66 @@
+// Device helpers shared by the bf16 MFMA attention kernels (gfx950).
+#ifndef PV_ATTN_COMMON_H_
+#define PV_ATTN_COMMON_H_
+
+#include <type_traits>
+
+#include "pv_internal.h"
+
+namespace pv {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+
+__device__ __forceinline__ unsigned pack_bf16(float a, float b) {
+  f32x2 v = {a, b};
+  bf16x2 r = __builtin_convertvector(v, bf16x2);   // round to nearest even
+  return __builtin_bit_cast(unsigned, r);
+}
+__device__ __forceinline__ float bf16_lo(unsigned u) { return __uint_as_float(u << 16); }
+__device__ __forceinline__ float bf16_hi(unsigned u) { return __uint_as_float(u & 0xffff0000u); }
+
+__device__ __forceinline__ bf16x8 as_bf16x8(uint4 u) { return __builtin_bit_cast(bf16x8, u); }
+
+// Value held by the lane 32 away (both halves get the other's value via max/sum of the pair).
+__device__ __forceinline__ float pair_max(float x) {
+  const unsigned u = __float_as_uint(x);
+  auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float pair_sum(float x) {
+  const unsigned u = __float_as_uint(x);
+  auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
+// 16-byte LDS read issued as inline assembly: the compiler neither tracks it nor orders it against
+// the global->LDS staging loads (its own LDS reads would wait for every outstanding staging load).
+// The caller must execute LDS_WAIT on the destination registers before using them.
+template <int OFF>
+__device__ __forceinline__ bf16x8 lds_read_b128(unsigned addr) {
+  bf16x8 r;
+  asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(r) : "v"(addr), "n"(OFF));
+  return r;
+}
+template <int I, int N, typename F>
+__device__ __forceinline__ void static_for(F&& f) {
+  if constexpr (I < N) {
+    f(std::integral_constant<int, I>{});
+    static_for<I + 1, N>(f);
+  }
+}
+
+// s_waitcnt immediate (gfx9 encoding) that waits for vmcnt <= n only.
+__host__ __device__ constexpr int vmcnt_imm(int n) { return 0x0f70 | (n & 15) | ((n >> 4) << 14); }
+
+// Launcher of the kernel with 64 query rows per wave (one wave per SIMD); returns
+// hipErrorNotSupported for shapes it does not cover (the caller then uses the generic kernel).
+hipError_t launch_attn_m64(const int32_t* plan, const PlanHeader& h, const uint16_t* q,
+                           const uint16_t* krot, const uint16_t* vt, const float2* cs, void* out,
+                           float* lse, int hq, int hkv, int d, float qscale, bool rope,
+                           bool out_f32, hipStream_t s);
+
+}  // namespace pv
+#endif
