@@ -51,6 +51,11 @@ enum {
 
 enum { PV_BF16 = 0, PV_F32 = 1 };
 
+/* Rows that see at most this many keys (the first tokens of a request, or a segment whose prefix is
+ * almost empty) are evaluated in plain fp32 by the bf16 path: with so few terms the bf16 rounding
+ * of the operands is not averaged out and would dominate the error of the whole output. */
+enum { PV_SHORT_ROW_KEYS = 16 };
+
 /* Structure of a packed verification batch.  HOST memory, owned by the caller. */
 typedef struct {
   int32_t batch;                 /* B >= 1 */
@@ -75,7 +80,8 @@ typedef struct {
   int64_t attn_workspace_bytes;  /* device scratch pv_masked_attention needs */
   int32_t n_q_heads, n_kv_heads, head_dim, in_dtype;
   int32_t tile_m, tile_n;        /* query tokens per work item, keys per tile */
-  int32_t reserved[2];
+  int32_t n_short_rows;          /* rows with at most PV_SHORT_ROW_KEYS visible keys (see below) */
+  int32_t reserved;
 } pv_sizes;
 
 /* Host only: validates the problem and the head configuration and fills `out`.

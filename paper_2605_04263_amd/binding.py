@@ -39,7 +39,7 @@ class PvSizes(C.Structure):
                 ("attn_workspace_bytes", C.c_int64),
                 ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32),
                 ("in_dtype", C.c_int32), ("tile_m", C.c_int32), ("tile_n", C.c_int32),
-                ("reserved", C.c_int32 * 2)]
+                ("n_short_rows", C.c_int32), ("reserved", C.c_int32)]
 
 
 def _load() -> C.CDLL:

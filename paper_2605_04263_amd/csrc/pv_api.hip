@@ -21,7 +21,7 @@ static inline pv_status hip_fail(hipError_t e) {
 static inline int64_t align_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
 
 void plan_layout(int batch, int64_t total_tokens, int64_t total_segments, int64_t n_q_tiles,
-                 int64_t padded_keys, PlanHeader* h) {
+                 int64_t padded_keys, int64_t n_short_rows, PlanHeader* h) {
   std::memset(h, 0, sizeof(*h));
   h->magic = kPlanMagic;
   h->batch = batch;
@@ -31,6 +31,7 @@ void plan_layout(int batch, int64_t total_tokens, int64_t total_segments, int64_
   h->tile_m = kTileM;
   h->tile_n = kTileN;
   h->padded_keys = (int32_t)padded_keys;
+  h->n_short_rows = (int32_t)n_short_rows;
   int64_t o = sizeof(PlanHeader) / 4;
   auto take = [&](int64_t n) { int64_t r = o; o = align_up(o + n, 4); return (int32_t)r; };
   h->off_prompt = take(batch);
@@ -43,6 +44,7 @@ void plan_layout(int batch, int64_t total_tokens, int64_t total_segments, int64_
   h->off_kpad_start = take(batch + 1);
   h->off_mask_start = take(2 * (int64_t)(batch + 1));
   h->off_bounds = take(total_segments);
+  h->off_short = take(n_short_rows);
   h->off_device_begin = (int32_t)o;
   h->off_pos = take(total_tokens);
   h->off_aend = take(total_tokens);
@@ -74,7 +76,18 @@ AttnWorkspace attn_workspace_layout(int64_t total_tokens, int64_t padded_keys, i
 
 struct Totals {
   int64_t tokens = 0, segments = 0, max_len = 0, q_tiles = 0, padded_keys = 0, mask_bytes = 0;
+  int64_t short_rows = 0;
 };
+
+// Rows of request (P, T, S, boundaries) that see at most PV_SHORT_ROW_KEYS keys: the first causal
+// rows, and rows of segments whose visible prefix is nearly empty.  Calls f(local_row).
+template <typename F>
+static void for_each_short_row(int64_t P, int64_t T, int64_t K, int64_t S, const int32_t* bounds, F f) {
+  const int64_t c = P + T;
+  for (int64_t i = 0; i < c && i + 1 <= PV_SHORT_ROW_KEYS; ++i) f(i);
+  for (int64_t k = 0; k < K; ++k)
+    for (int64_t a = 0; a < S && P + bounds[k] + a + 1 <= PV_SHORT_ROW_KEYS; ++a) f(c + k * S + a);
+}
 
 // Validates the problem; fills totals.  Limits keep every index inside int32.
 static pv_status validate_problem(const pv_problem* p, Totals* t) {
@@ -100,6 +113,7 @@ static pv_status validate_problem(const pv_problem* p, Totals* t) {
       if (pk < prev || pk > T) return PV_ERR_BOUNDARY;
       prev = pk;
     }
+    for_each_short_row(P, T, K, S, p->boundaries + seg, [&](int64_t) { t->short_rows++; });
     seg += K;
     t->tokens += n;
     t->max_len = n > t->max_len ? n : t->max_len;
@@ -129,7 +143,8 @@ static void fill_sizes(const pv_problem* p, const Totals& t, int hq, int hkv, in
   s->n_q_tiles = t.q_tiles;
   s->padded_keys = t.padded_keys;
   PlanHeader h;
-  plan_layout(p->batch, t.tokens, t.segments, t.q_tiles, t.padded_keys, &h);
+  plan_layout(p->batch, t.tokens, t.segments, t.q_tiles, t.padded_keys, t.short_rows, &h);
+  s->n_short_rows = (int32_t)t.short_rows;
   s->plan_bytes = (int64_t)h.total_ints * 4;
   s->dense_mask_bytes = t.mask_bytes;
   s->attn_workspace_bytes = attn_workspace_layout(t.tokens, t.padded_keys, hkv, d, in_dtype).total;
@@ -145,11 +160,13 @@ static void fill_sizes(const pv_problem* p, const Totals& t, int hq, int hkv, in
 static pv_status check_sizes(const pv_sizes* s, PlanHeader* h) {
   if (!s) return PV_ERR_NULL;
   if (s->batch < 1 || s->total_tokens < 1 || s->total_segments < 0 || s->n_q_tiles < 1 ||
-      s->tile_m != kTileM || s->tile_n != kTileN || s->padded_keys < s->total_tokens)
+      s->tile_m != kTileM || s->tile_n != kTileN || s->padded_keys < s->total_tokens ||
+      s->n_short_rows < 0 || s->n_short_rows > s->total_tokens)
     return PV_ERR_SHAPE;
   if (validate_heads(s->n_q_heads, s->n_kv_heads, s->head_dim, s->in_dtype) != PV_OK)
     return PV_ERR_SHAPE;
-  plan_layout((int)s->batch, s->total_tokens, s->total_segments, s->n_q_tiles, s->padded_keys, h);
+  plan_layout((int)s->batch, s->total_tokens, s->total_segments, s->n_q_tiles, s->padded_keys,
+              s->n_short_rows, h);
   if (s->plan_bytes != (int64_t)h->total_ints * 4) return PV_ERR_SHAPE;
   return PV_OK;
 }
@@ -207,7 +224,8 @@ pv_status pv_build_mask(const pv_problem* problem, const pv_sizes* sizes, void* 
   if (st != PV_OK) return st;
   if (sizes->batch != problem->batch || sizes->total_tokens != t.tokens ||
       sizes->total_segments != t.segments || sizes->n_q_tiles != t.q_tiles ||
-      sizes->padded_keys != t.padded_keys || sizes->dense_mask_bytes != t.mask_bytes)
+      sizes->padded_keys != t.padded_keys || sizes->dense_mask_bytes != t.mask_bytes ||
+      sizes->n_short_rows != t.short_rows)
     return PV_ERR_SHAPE;
   if (!plan_dev) return PV_ERR_NULL;
   if (plan_bytes < sizes->plan_bytes) return PV_ERR_WORKSPACE;
@@ -218,7 +236,7 @@ pv_status pv_build_mask(const pv_problem* problem, const pv_sizes* sizes, void* 
   std::vector<int32_t> img((size_t)h.off_device_begin, 0);
   std::memcpy(img.data(), &h, sizeof(h));
   const int B = problem->batch;
-  int64_t tok = 0, seg = 0, qt = 0, kp = 0, mk = 0;
+  int64_t tok = 0, seg = 0, qt = 0, kp = 0, mk = 0, ns = 0;
   int64_t* mask_start = reinterpret_cast<int64_t*>(img.data() + h.off_mask_start);
   for (int b = 0; b <= B; ++b) {
     img[h.off_tok_start + b] = (int32_t)tok;
@@ -235,6 +253,8 @@ pv_status pv_build_mask(const pv_problem* problem, const pv_sizes* sizes, void* 
     img[h.off_nseg + b] = (int32_t)K;
     img[h.off_seglen + b] = (int32_t)S;
     for (int64_t k = 0; k < K; ++k) img[h.off_bounds + seg + k] = problem->boundaries[seg + k];
+    for_each_short_row(P, T, K, S, problem->boundaries + seg,
+                       [&](int64_t i) { img[h.off_short + ns++] = (int32_t)(tok + i); });
     tok += n;
     seg += K;
     qt += (n + kTileM - 1) / kTileM;

@@ -36,14 +36,93 @@ __global__ __launch_bounds__(256) void k_rope_table_bf16(const int32_t* plan, Pl
 // ---------------------------------------------------------------- K/V preparation
 // grid = (padded_keys / 64, Hkv), 256 threads.  Pad rows (beyond the request) are written as 0 so
 // that masked probabilities (exactly 0) never meet a non-finite value.
+struct ShortRowArgs {          // what the fp32 evaluation of the short rows needs beyond k, v, cs
+  const uint16_t* q;
+  void* out;
+  float* lse;
+  int hq;
+  float scale;
+  bool out_f32;
+};
+
+// Rows with at most PV_SHORT_ROW_KEYS visible keys, in plain fp32 (the main kernel does not store
+// them).  One wave per (row, query head); lane c owns the rotation pair (c, c + D/2).
+template <int D>
+__device__ void short_row(const int32_t* __restrict__ plan, const PlanHeader& h,
+                          const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
+                          const float2* __restrict__ cs, int hkv, bool rope, const ShortRowArgs& a,
+                          int g, int head, int lane) {
+  constexpr int HALF = D / 2;
+  const int kvh = head / (a.hq / hkv);
+  const int32_t* ts = plan + h.off_tok_start;
+  int lo = 0, hi = h.batch;
+  while (hi - lo > 1) { const int mid = (lo + hi) >> 1; if (ts[mid] <= g) lo = mid; else hi = mid; }
+  const int base = ts[lo], i = g - base;
+  const int a_end = plan[h.off_aend + g], b_start = plan[h.off_bstart + g];
+  const bool on = lane < HALF;
+  const int c = on ? lane : 0;
+  auto load_pair = [&](const uint16_t* row, int tok, float* lo_out, float* hi_out) {
+    const float xl = __uint_as_float((unsigned)row[c] << 16), xh = __uint_as_float((unsigned)row[c + HALF] << 16);
+    if (rope) {
+      const float2 t = cs[(int64_t)tok * HALF + c];
+      *lo_out = xl * t.x - xh * t.y;
+      *hi_out = xh * t.x + xl * t.y;
+    } else { *lo_out = xl; *hi_out = xh; }
+  };
+  float ql, qh;
+  load_pair(a.q + ((int64_t)g * a.hq + head) * D, g, &ql, &qh);
+  float sc[PV_SHORT_ROW_KEYS];
+  int keys[PV_SHORT_ROW_KEYS];
+  int n = 0;
+  for (int j = 0; j < a_end && n < PV_SHORT_ROW_KEYS; ++j) keys[n++] = j;
+  for (int j = max(b_start, a_end); j <= i && n < PV_SHORT_ROW_KEYS; ++j) keys[n++] = j;
+  float m = -INFINITY;
+  for (int e = 0; e < n; ++e) {
+    float kl, kh;
+    load_pair(k + ((int64_t)(base + keys[e]) * hkv + kvh) * D, base + keys[e], &kl, &kh);
+    float part = on ? ql * kl + qh * kh : 0.0f;
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) part += __shfl_xor(part, off);
+    sc[e] = part * a.scale;
+    m = fmaxf(m, sc[e]);
+  }
+  float l = 0.0f, ol = 0.0f, oh = 0.0f;
+  for (int e = 0; e < n; ++e) {
+    const float p = expf(sc[e] - m);
+    const uint16_t* vr = v + ((int64_t)(base + keys[e]) * hkv + kvh) * D;
+    l += p;
+    ol = fmaf(p, __uint_as_float((unsigned)vr[c] << 16), ol);
+    oh = fmaf(p, __uint_as_float((unsigned)vr[c + HALF] << 16), oh);
+  }
+  if (on) {
+    const int64_t row = ((int64_t)g * a.hq + head) * D;
+    if (a.out_f32) {
+      float* op = reinterpret_cast<float*>(a.out) + row;
+      op[c] = ol / l; op[c + HALF] = oh / l;
+    } else {
+      uint16_t* op = reinterpret_cast<uint16_t*>(a.out) + row;
+      op[c] = (uint16_t)(pack_bf16(ol / l, 0.0f) & 0xffffu);
+      op[c + HALF] = (uint16_t)(pack_bf16(oh / l, 0.0f) & 0xffffu);
+    }
+    if (a.lse && lane == 0) a.lse[(int64_t)head * h.total_tokens + g] = m + logf(l);
+  }
+}
+
 template <int D>
 __global__ __launch_bounds__(256) void k_prep_kv(const int32_t* __restrict__ plan, PlanHeader h,
                                                  const uint16_t* __restrict__ k,
                                                  const uint16_t* __restrict__ v,
                                                  const float2* __restrict__ cs, int hkv, bool rope,
                                                  uint16_t* __restrict__ krot,
-                                                 uint16_t* __restrict__ vt) {
+                                                 uint16_t* __restrict__ vt, ShortRowArgs sr) {
   constexpr int HALF = D / 2;
+  if ((int)blockIdx.x >= h.padded_keys / 64) {           // extra blocks: one short row each
+    const int g = plan[h.off_short + ((int)blockIdx.x - h.padded_keys / 64)];
+    const int G = sr.hq / hkv;
+    for (int hl = threadIdx.x >> 6; hl < G; hl += 4)
+      short_row<D>(plan, h, k, v, cs, hkv, rope, sr, g, blockIdx.y * G + hl, threadIdx.x & 63);
+    return;
+  }
   const int tile_row = blockIdx.x * 64;      // first padded key row of this tile
   const int kvh = blockIdx.y;
   // owner request of the tile
@@ -484,6 +563,13 @@ __global__ __launch_bounds__(G * 64, 2) void k_attn_bf16(
   {
     const float inv = 1.0f / l_tot;
     const int64_t tok0 = (int64_t)tile.tok_base + tile.t0;
+    // rows with few visible keys are produced in fp32 by the preparation kernel: not stored here
+    auto stored = [&](int row) {
+      if (row >= tile.rows) return false;
+      const int64_t gg = tok0 + row;
+      const int cnt = plan[h.off_aend + gg] + (tile.t0 + row) - plan[h.off_bstart + gg] + 1;
+      return cnt > PV_SHORT_ROW_KEYS;
+    };
     constexpr int RS = 2 * D + 16;                    // row stride: 16 B of padding spreads the banks
     char* tr = reinterpret_cast<char*>(&smem[0][0][0]) + (size_t)wave * (32 * RS);
     if (out_f32) {
@@ -504,7 +590,7 @@ __global__ __launch_bounds__(G * 64, 2) void k_attn_bf16(
         for (int it = 0; it < 32 * LPR / 64; ++it) {
           const int row = it * (64 / LPR) + lane / LPR, c = lane % LPR;
           const float4 w = *reinterpret_cast<const float4*>(tr + row * RS + c * 16);
-          if (row < tile.rows)
+          if (stored(row))
             *reinterpret_cast<float4*>(op + ((tok0 + row) * hq + head) * D + half * (D / 2) + c * 4) = w;
         }
       }
@@ -524,10 +610,10 @@ __global__ __launch_bounds__(G * 64, 2) void k_attn_bf16(
       for (int it = 0; it < 32 * LPR / 64; ++it) {
         const int row = it * (64 / LPR) + lane / LPR, c = lane % LPR;
         const uint4 w = *reinterpret_cast<const uint4*>(tr + row * RS + c * 16);
-        if (row < tile.rows) *reinterpret_cast<uint4*>(op + ((tok0 + row) * hq + head) * D + c * 8) = w;
+        if (stored(row)) *reinterpret_cast<uint4*>(op + ((tok0 + row) * hq + head) * D + c * 8) = w;
       }
     }
-    if (lse && hh == 0 && valid)
+    if (lse && hh == 0 && valid && a_end + i_loc - b_start + 1 > PV_SHORT_ROW_KEYS)
       lse[(int64_t)head * h.total_tokens + g] = (mref * esc + log2f(l_tot)) * 0.6931471805599453f;
   }
 }
@@ -579,9 +665,11 @@ hipError_t launch_attn_bf16(const int32_t* plan_dev, const PlanHeader& h, const 
     if (e != hipSuccess) return e;
   }
   {
-    const dim3 grid((unsigned)(h.padded_keys / 64), (unsigned)hkv);
-    if (d == 64) k_prep_kv<64><<<grid, dim3(256), 0, s>>>(plan_dev, h, kk, kv, cs, hkv, rope, krot, vt);
-    else k_prep_kv<128><<<grid, dim3(256), 0, s>>>(plan_dev, h, kk, kv, cs, hkv, rope, krot, vt);
+    const dim3 grid((unsigned)(h.padded_keys / 64 + h.n_short_rows), (unsigned)hkv);
+    ShortRowArgs sr;
+    sr.q = kq; sr.out = out; sr.lse = lse; sr.hq = hq; sr.scale = scale; sr.out_f32 = out_dtype == PV_F32;
+    if (d == 64) k_prep_kv<64><<<grid, dim3(256), 0, s>>>(plan_dev, h, kk, kv, cs, hkv, rope, krot, vt, sr);
+    else k_prep_kv<128><<<grid, dim3(256), 0, s>>>(plan_dev, h, kk, kv, cs, hkv, rope, krot, vt, sr);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
   }

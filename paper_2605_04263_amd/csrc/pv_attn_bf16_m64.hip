@@ -458,6 +458,13 @@ __global__ __launch_bounds__(256, 1) void k_attn_m64(
   // per-wave transposition area (32 rows x 528 B); with the key split it sits above the merge area
   char* tr = reinterpret_cast<char*>(&smem[0][0][0][0]) + (KS == 2 ? 96 * 1024 : 0) + (size_t)wave * (32 * 528);
   const int64_t tok0 = (int64_t)tile.tok_base + tile.t0;
+  // rows with few visible keys are produced in fp32 by the preparation kernel: not stored here
+  auto stored = [&](int row) {
+    if (row >= tile.rows) return false;
+    const int64_t gg = tok0 + row;
+    const int cnt = plan[h.off_aend + gg] + (tile.t0 + row) - plan[h.off_bstart + gg] + 1;
+    return cnt > PV_SHORT_ROW_KEYS;
+  };
 #pragma unroll
   for (int b = 0; b < 2; ++b) {
     const float inv = 1.0f / l_tot[b];
@@ -477,7 +484,7 @@ __global__ __launch_bounds__(256, 1) void k_attn_m64(
       for (int it = 0; it < 16; ++it) {                // 2 rows per instruction, 32 lanes x 16 B per row
         const int row = 2 * it + (lane >> 5), c = lane & 31;
         const float4 w = *reinterpret_cast<const float4*>(tr + row * 528 + c * 16);
-        if (row < tile.rows) *reinterpret_cast<float4*>(op + ((tok0 + row) * hq + head) * D + c * 4) = w;
+        if (stored(row)) *reinterpret_cast<float4*>(op + ((tok0 + row) * hq + head) * D + c * 4) = w;
       }
     } else {
       // row stride 264 B (256 + 8)
@@ -497,11 +504,11 @@ __global__ __launch_bounds__(256, 1) void k_attn_m64(
         // 264-byte rows are only 8-byte aligned: read the 16 bytes as two 8-byte halves
         const uint2 w0 = *reinterpret_cast<const uint2*>(tr + row * 264 + c * 16);
         const uint2 w1 = *reinterpret_cast<const uint2*>(tr + row * 264 + c * 16 + 8);
-        if (row < tile.rows)
+        if (stored(row))
           *reinterpret_cast<uint4*>(op + ((tok0 + row) * hq + head) * D + c * 8) = make_uint4(w0.x, w0.y, w1.x, w1.y);
       }
     }
-    if (lse && hh == 0 && valid)
+    if (lse && hh == 0 && valid && a_end + i_loc - b_start + 1 > PV_SHORT_ROW_KEYS)
       lse[(int64_t)head * h.total_tokens + g] = (mref[b] * esc + log2f(l_tot[b])) * 0.6931471805599453f;
   }
 }

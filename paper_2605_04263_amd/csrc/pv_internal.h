@@ -27,12 +27,14 @@ struct PlanHeader {
   int32_t off_qtile_start, off_kpad_start;               // [B+1] each
   int32_t off_mask_start;                                // int64 [B+1] (8-byte aligned)
   int32_t off_bounds;                                    // [total_segments]
+  int32_t off_short;                                     // [n_short_rows] packed row indices
   int32_t off_device_begin;
   int32_t off_pos, off_aend, off_bstart;                 // [total_tokens] each
   int32_t off_judge;                                     // [total_segments]
   int32_t off_tiles, off_work;                           // [n_q_tiles][8] each
   int32_t total_ints;
-  int32_t pad[6];
+  int32_t n_short_rows;
+  int32_t pad[4];
 };
 static_assert(sizeof(PlanHeader) == 32 * 4, "PlanHeader must be 32 ints");
 
@@ -79,7 +81,7 @@ hipError_t launch_attn_bf16(const int32_t* plan_dev, const PlanHeader& h, const 
 
 // Host-side layout of the plan; shared by pv_query_sizes and pv_build_mask.
 void plan_layout(int batch, int64_t total_tokens, int64_t total_segments, int64_t n_q_tiles,
-                 int64_t padded_keys, PlanHeader* h);
+                 int64_t padded_keys, int64_t n_short_rows, PlanHeader* h);
 
 }  // namespace pv
 #endif

@@ -2,7 +2,8 @@
 
 Tolerance (bf16 inputs): max-abs <= 1e-2 and mean-abs <= 1e-3 against the un-rounded oracle for
 the fp32-output run (the kernel's own arithmetic); the bf16-output run must equal that result
-rounded to nearest even, which adds at most half a bf16 ulp of the value.
+rounded to nearest even, which adds at most half a bf16 ulp of the value.  Rows that see at most
+PV_SHORT_ROW_KEYS keys are evaluated in fp32 by the library and are far inside the tolerance.
 Small cases compare every element; the large named configs compare oracle-computed sampled rows
 (every row is independent given K/V, so a subset is exact)."""
 import numpy as np
@@ -40,15 +41,6 @@ def check_errors(got, ref, bf16_out, max_abs=MAX_ABS):
     else:
         assert err.max() <= max_abs, err.max()
     return err.max(), err.mean()
-
-
-def edge_max_abs(w):
-    """Bound for the synthetic edge shapes, which are dominated by rows with a handful of keys.
-    bf16 operands give every softmax weight a relative error of up to about 2^-8 (rounding of the
-    probabilities, and of the rotated Q/K through the scores); the output moves by that times the
-    spread of the V rows it mixes, at most 2 max|V|.  The stated 1e-2 is kept as the floor and is
-    what the five named configs are held to."""
-    return max(MAX_ABS, 2.0 ** -8 * float(w.v.float().abs().max()))
 
 
 def check_full(w, max_abs=MAX_ABS):
@@ -102,7 +94,7 @@ EDGE = [
 def test_edge_cases(idx):
     pr, hq, hkv, d, theta = EDGE[idx]
     w = wl.make_custom(pr, hq, hkv, d, dtype=torch.bfloat16, rope_theta=theta, seed=100 + idx)
-    check_full(w, max_abs=edge_max_abs(w))
+    check_full(w)
 
 
 def test_tiny_shape_in_bf16():
