@@ -71,28 +71,38 @@ __device__ void short_row(const int32_t* __restrict__ plan, const PlanHeader& h,
   };
   float ql, qh;
   load_pair(a.q + ((int64_t)g * a.hq + head) * D, g, &ql, &qh);
+  // Visible keys: [0, a_end) then [max(b_start, a_end), i]; at most PV_SHORT_ROW_KEYS of them.
+  // All loads are issued before any of them is used (fixed trip count, predicated).
+  const int n_a = min(a_end, (int)PV_SHORT_ROW_KEYS);
+  const int b0 = max(b_start, a_end);
+  const int n = min(n_a + max(i - b0 + 1, 0), (int)PV_SHORT_ROW_KEYS);
+  float kl[PV_SHORT_ROW_KEYS], kh[PV_SHORT_ROW_KEYS], vl[PV_SHORT_ROW_KEYS], vh[PV_SHORT_ROW_KEYS];
+#pragma unroll
+  for (int e = 0; e < PV_SHORT_ROW_KEYS; ++e) {
+    const int key = e < n_a ? e : b0 + (e - n_a);
+    const int tok = base + (e < n ? key : i);           // clamp to a valid row when predicated off
+    load_pair(k + ((int64_t)tok * hkv + kvh) * D, tok, &kl[e], &kh[e]);
+    const uint16_t* vr = v + ((int64_t)tok * hkv + kvh) * D;
+    vl[e] = __uint_as_float((unsigned)vr[c] << 16);
+    vh[e] = __uint_as_float((unsigned)vr[c + HALF] << 16);
+  }
   float sc[PV_SHORT_ROW_KEYS];
-  int keys[PV_SHORT_ROW_KEYS];
-  int n = 0;
-  for (int j = 0; j < a_end && n < PV_SHORT_ROW_KEYS; ++j) keys[n++] = j;
-  for (int j = max(b_start, a_end); j <= i && n < PV_SHORT_ROW_KEYS; ++j) keys[n++] = j;
   float m = -INFINITY;
-  for (int e = 0; e < n; ++e) {
-    float kl, kh;
-    load_pair(k + ((int64_t)(base + keys[e]) * hkv + kvh) * D, base + keys[e], &kl, &kh);
-    float part = on ? ql * kl + qh * kh : 0.0f;
+#pragma unroll
+  for (int e = 0; e < PV_SHORT_ROW_KEYS; ++e) {
+    float part = on ? ql * kl[e] + qh * kh[e] : 0.0f;
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) part += __shfl_xor(part, off);
-    sc[e] = part * a.scale;
+    sc[e] = e < n ? part * a.scale : -INFINITY;
     m = fmaxf(m, sc[e]);
   }
   float l = 0.0f, ol = 0.0f, oh = 0.0f;
-  for (int e = 0; e < n; ++e) {
-    const float p = expf(sc[e] - m);
-    const uint16_t* vr = v + ((int64_t)(base + keys[e]) * hkv + kvh) * D;
+#pragma unroll
+  for (int e = 0; e < PV_SHORT_ROW_KEYS; ++e) {
+    const float p = expf(sc[e] - m);                    // exp(-inf) = 0 for the unused slots
     l += p;
-    ol = fmaf(p, __uint_as_float((unsigned)vr[c] << 16), ol);
-    oh = fmaf(p, __uint_as_float((unsigned)vr[c + HALF] << 16), oh);
+    ol = fmaf(p, vl[e], ol);
+    oh = fmaf(p, vh[e], oh);
   }
   if (on) {
     const int64_t row = ((int64_t)g * a.hq + head) * D;
