@@ -14,9 +14,6 @@
 // of the online softmax is a per-lane scalar.  O^T = V^T P^T then takes P^T straight from the
 // accumulator registers of S^T (the key order inside a slab is chosen to make that a pure
 // register repack).
-#include <cstdlib>
-#include <cstring>
-
 #include "pv_attn_common.h"
 
 namespace pv {
@@ -171,9 +168,12 @@ __global__ __launch_bounds__(256) void k_prep_kv(const int32_t* __restrict__ pla
         }
       }
     }
-    uint16_t* dst = krot + out_base + (int64_t)key * D;
-    *reinterpret_cast<uint4*>(dst + c0) = lo4;
-    *reinterpret_cast<uint4*>(dst + c0 + HALF) = hi4;
+    // operand order: inside a block of 32 keys, chunk (t, hh, row) = features 16 t + 8 hh .. + 7
+    // of key `row` sits at chunk index t * 64 + hh * 32 + row
+    uint4* dst = reinterpret_cast<uint4*>(krot + out_base) + (key >> 5) * (32 * D / 8) + (key & 31);
+    const int ci = c0 >> 3;                       // chunk of the low half; the high one is D/16 later
+    dst[(ci >> 1) * 64 + (ci & 1) * 32] = lo4;
+    dst[((ci + D / 16) >> 1) * 64 + ((ci + D / 16) & 1) * 32] = hi4;
   }
 
   // V^T: slab s (16 keys) is [2][D][8]; element (hh, d, m) is key 8*(m/4) + 4*hh + (m%4) of the
@@ -198,24 +198,23 @@ __global__ __launch_bounds__(256) void k_prep_kv(const int32_t* __restrict__ pla
 // is free when Q is rotated anyway.  Without rotation Q enters the MFMA exactly as given and the
 // scale multiplies the fp32 score inside the exponent instead.
 template <int D, int G, bool FOLD>
-__global__ __launch_bounds__(G * 64, 2) void k_attn_bf16(
+__global__ __launch_bounds__(G * 64, 2) __attribute__((amdgpu_waves_per_eu(2))) void k_attn_bf16(
     const int32_t* __restrict__ plan, PlanHeader h, const uint16_t* __restrict__ q,
     const uint16_t* __restrict__ krot, const uint16_t* __restrict__ vt,
     const float2* __restrict__ cs, void* __restrict__ out, float* __restrict__ lse, int hq, int hkv,
     float qscale, bool rope, bool out_f32) {
-  constexpr int NT = G * 64;
   constexpr int KT = D / 16;            // MFMA steps along the feature dim for S^T
   constexpr int DB = D / 32;            // 32-feature blocks of O^T
-  constexpr int CH32 = 32 * D / 8;      // 16-byte chunks per 32-key K (or V^T) stage
+  constexpr int CH32 = 32 * D / 8;      // 16-byte chunks per 32-key K (or V^T) slot
   constexpr int CPR = D / 8;            // chunks per key row
-  constexpr int NS = (D == 128) ? 5 : 8;                 // LDS stages of 32 keys (K and V^T each)
-  constexpr int LPS = 2 * ((CH32 / 64) / G);             // staging loads every wave issues per stage
+  constexpr int NS = (D == 128) ? 5 : 8;                 // slots per ring (32 keys each)
+  constexpr int HPW = (CH32 / 64) / G;                   // staging loads every wave issues per slot
+  constexpr unsigned SLOT_BYTES = CH32 * 16;
   // One LDS array on purpose: with several LDS variables the compiler attaches alias scopes and
   // then makes every LDS read wait for all outstanding global->LDS loads, which would serialise
   // the staging pipeline.  Ordering is enforced here with explicit vmcnt waits and barriers.
-  __shared__ uint4 smem[NS][2][CH32];
-#define sK(buf) smem[buf][0]
-#define sV(buf) smem[buf][1]
+  // Layout: K ring (NS slots), then V^T ring (NS slots).  Step s lives in slot s % NS of each.
+  __shared__ uint4 smem[2 * NS * CH32];
 
   const int kvh = blockIdx.x % hkv;
   const QTile tile = reinterpret_cast<const QTile*>(plan + h.off_work)[blockIdx.x / hkv];
@@ -231,9 +230,10 @@ __global__ __launch_bounds__(G * 64, 2) void k_attn_bf16(
   bf16x8 qf[KT];          // Q operand of this wave's head (filled below, once the tile is in LDS)
 
   // ---- key steps.  A key tile of the plan (64 keys) is two steps of 32 keys; tiles run over
-  // [0, n_a) then [jb0, jb1).  Step j lives in LDS stage j % NS.
+  // [0, n_a) then [jb0, jb1).  The number of steps is even.
   const int n_tiles = tile.n_a + (tile.jb1 - tile.jb0);
   const int n_steps = 2 * n_tiles;
+  const int last = n_steps - 1;
   const int64_t head_base = ((int64_t)kvh * h.padded_keys + tile.kpad_base) * D;   // elements
   auto step_key0 = [&](int j) {           // first key (request-local) of step j
     const int idx = j >> 1;
@@ -241,62 +241,58 @@ __global__ __launch_bounds__(G * 64, 2) void k_attn_bf16(
     return jt * 64 + (j & 1) * 32;
   };
   // Direct global->LDS staging: a wave instruction moves 64 consecutive 16-byte chunks, lane l
-  // landing at chunk (base + l).  The K bank swizzle (chunk pos ^ row within each 256-byte row)
-  // is applied by choosing which global chunk a lane fetches.
+  // landing at chunk (base + l).  Both workspaces are already in MFMA operand order, so a slot is
+  // a plain copy and operand reads are linear (lane l reads chunk l of its k-step: no conflicts).
   const int wave_s = __builtin_amdgcn_readfirstlane(wave);      // wave index as a scalar
   constexpr int NREP = (CH32 / 64 + G - 1) / G;                  // staging instructions per wave
-  unsigned gk_off[NREP], gv_off[NREP];                           // per-lane byte offsets in a stage
-#pragma unroll
-  for (int n = 0; n < NREP; ++n) {
-    const int P = (wave_s + n * G) * 64 + lane;
-    const int R = P >> 4, pos = P & 15;
-    gk_off[n] = (unsigned)(((R << 4) + (pos ^ (R & 15))) * 16);
-    gv_off[n] = (unsigned)(P * 16);
-  }
+  const unsigned lane16 = (unsigned)lane * 16;
   const unsigned smem_base =
-      (unsigned)(uintptr_t)(__attribute__((address_space(3))) char*)(char*)&smem[0][0][0];
-  constexpr unsigned STAGE_BYTES = 2 * CH32 * 16;
+      (unsigned)(uintptr_t)(__attribute__((address_space(3))) char*)(char*)&smem[0];
+  const unsigned vring = smem_base + NS * SLOT_BYTES;
   const char* krot_b = reinterpret_cast<const char*>(krot) + head_base * 2;
   const char* vt_b = reinterpret_cast<const char*>(vt) + head_base * 2;
-  // stage step j into LDS stage `buf` (scalar bases + per-lane offsets: a few scalar ops per step)
-  auto stage = [&](int j, int buf) {
-    if (j >= n_steps) return;
-    const int64_t off = (int64_t)step_key0(j) * (D * 2);
-    const char* gk = krot_b + off;
-    const char* gv = vt_b + off;
-    const unsigned lds0 = smem_base + (unsigned)buf * STAGE_BYTES;
+  // stage the K (or V^T) half of step s into its ring slot; nothing is issued beyond the last step
+  auto stage_slot = [&](const char* src, unsigned lds0) {
 #pragma unroll
     for (int n = 0; n < NREP; ++n) {
       const int c = wave_s + n * G;
       if ((CH32 / 64) % G != 0 && c >= CH32 / 64) break;
+      unsigned lo = lane16;
+      asm volatile("" : "+v"(lo));     // keeps the address in (scalar base + 32-bit lane offset) form
       __builtin_amdgcn_global_load_lds(
-          (const __attribute__((address_space(1))) void*)(gk + gk_off[n]),
+          (const __attribute__((address_space(1))) void*)(src + c * 1024 + lo),
           (__attribute__((address_space(3))) void*)(uintptr_t)(lds0 + c * 1024), 16, 0, 0);
-      __builtin_amdgcn_global_load_lds(
-          (const __attribute__((address_space(1))) void*)(gv + gv_off[n]),
-          (__attribute__((address_space(3))) void*)(uintptr_t)(lds0 + CH32 * 16 + c * 1024), 16, 0, 0);
     }
+  };
+  auto stage_k = [&](int s) {
+    if (s > last) return;
+    stage_slot(krot_b + (int64_t)step_key0(s) * (D * 2), smem_base + (unsigned)(s % NS) * SLOT_BYTES);
+  };
+  auto stage_v = [&](int s) {
+    if (s > last) return;
+    stage_slot(vt_b + (int64_t)step_key0(s) * (D * 2), vring + (unsigned)(s % NS) * SLOT_BYTES);
+  };
+  // wait until at most n slots' worth of this wave's staging loads are outstanding (every wave
+  // issues at least HPW loads per slot, so n * HPW never exceeds what is really in flight)
+  auto wait_slots = [&](auto max_n, int n) {           // n <= max_n
+    constexpr int MAXN = decltype(max_n)::value;
+    bool done = false;
+    static_for<0, MAXN>([&](auto c) {
+      constexpr int v = MAXN - decltype(c)::value;
+      if constexpr (v * HPW <= 63) {
+        if (!done && n >= v) { __builtin_amdgcn_s_waitcnt(vmcnt_imm(v * HPW)); done = true; }
+      }
+    });
+    if (!done) __builtin_amdgcn_s_waitcnt(0x0f70);
   };
   bf16x8 kf[KT];          // K operand of the next S^T
   bf16x8 vf[2][DB];       // V^T operands of the current step
-  // per-lane LDS byte offsets inside a stage (the K swizzle makes them lane dependent per k-step)
-  unsigned k_off[KT];
-#pragma unroll
-  for (int t = 0; t < KT; ++t) {
-    const int L = qrow * CPR + 2 * t + hh;
-    const int R = L >> 4, pos = L & 15;
-    k_off[t] = smem_base + (unsigned)(((R << 4) + (pos ^ (R & 15))) * 16);
-  }
-  const unsigned v_off = smem_base + (unsigned)((CH32 + hh * D + qrow) * 16);
-  auto load_k = [&](int buf) {
-    const unsigned sb = (unsigned)buf * STAGE_BYTES;
-    static_for<0, KT>([&](auto t) { kf[t] = lds_read_b128<0>(k_off[t] + sb); });
-  };
-  auto load_v = [&](int buf) {
-    const unsigned a = v_off + (unsigned)buf * STAGE_BYTES;
-    static_for<0, 2>([&](auto uu) {
-      static_for<0, DB>([&](auto db) { vf[uu][db] = lds_read_b128<(uu * 2 * D + db * 32) * 16>(a); });
-    });
+  // per-lane LDS byte addresses inside slot 0: k-step t of K is 1 KB further per t
+  const unsigned k_off = smem_base + lane16;
+  const unsigned v_off = vring + (unsigned)((hh * D + qrow) * 16);
+  auto load_k = [&](int slot) {
+    const unsigned a = k_off + (unsigned)slot * SLOT_BYTES;
+    static_for<0, KT>([&](auto t) { kf[t] = lds_read_b128<decltype(t)::value * 1024>(a); });
   };
   auto wait_kv = [&]() {   // every outstanding LDS read of this wave has landed
     if constexpr (D == 128) {
@@ -326,12 +322,21 @@ __global__ __launch_bounds__(G * 64, 2) void k_attn_bf16(
 #pragma unroll
   for (int r = 0; r < 16; ++r) cinit[r] = 0.0f;
 
-  auto qk = [&]() {
-    asm volatile("" : "+v"(cinit));
-    f32x16 acc = cinit;
+  // First product of a score tile: accumulates on cinit but writes other registers, so that no
+  // copy of cinit is needed (the compiler's own form ties the result to the accumulator input).
+  // The instruction is opaque to the compiler's hazard handling.  Its inputs are written long
+  // before (LDS reads behind a wait, Q and cinit outside the block).  Its result must not be
+  // touched by a non-MFMA instruction for 8 passes + 3 wait states; normally the next product
+  // consumes it, but the register allocator may place a copy there (it does when the accumulators
+  // live in AGPRs), so the wait states are part of the statement.
+  auto qk_first = [&](f32x16& acc) {
+    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %3\n\ts_nop 7\n\ts_nop 7"
+                 : "=&v"(acc) : "v"(kf[0]), "v"(qf[0]), "v"(cinit));
+  };
+  auto qk = [&](f32x16& acc) {
+    qk_first(acc);
 #pragma unroll
-    for (int t = 0; t < KT; ++t) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[t], qf[t], acc, 0, 0, 0);
-    return acc;
+    for (int t = 1; t < KT; ++t) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[t], qf[t], acc, 0, 0, 0);
   };
   auto apply_mask = [&](f32x16& sc, int key0) {
 #pragma unroll
@@ -389,16 +394,19 @@ __global__ __launch_bounds__(G * 64, 2) void k_attn_bf16(
 
   // ---- Q tile (and its cos/sin rows) through LDS.  A lane needs 16-byte pieces of 32 different
   // rows, which as direct global loads is one cache line per lane; instead the waves copy whole
-  // rows with global->LDS loads (swizzled like K) into the stage memory, read their operands
-  // from there, and only then start the K/V staging.
+  // rows with global->LDS loads (swizzled like K) into the END of the ring memory, read their
+  // operands from there, and only then stage what belongs to that memory.  The K slots in front of
+  // that area are staged right away, so their latency overlaps that of the Q tile.
+  constexpr int QCH = G * 32 * CPR;                 // 16-byte chunks of the Q tile
+  constexpr int CSR = D / 4;                        // chunks per table row (D/2 float2)
+  constexpr int CSCH = 32 * CSR;
+  static_assert(QCH + CSCH <= 2 * NS * CH32, "Q tile and table must fit the rings");
+  constexpr int QAREA0 = 2 * NS * CH32 - (QCH + CSCH);            // first chunk of the area
+  constexpr int NK0 = (QAREA0 / CH32) < NS ? (QAREA0 / CH32) : NS;  // K slots free from the start
   {
-    constexpr int QCH = G * 32 * CPR;                 // 16-byte chunks of the Q tile
-    constexpr int CSR = D / 4;                        // chunks per table row (D/2 float2)
-    constexpr int CSCH = 32 * CSR;
-    static_assert((QCH + CSCH) * 16 <= NS * 2 * CH32 * 16, "Q tile and table must fit the stages");
     const int rows_m1 = tile.rows - 1;
     const int64_t tok0 = (int64_t)tile.tok_base + tile.t0;
-    const unsigned q_area = smem_base, cs_area = smem_base + QCH * 16;
+    const unsigned q_area = smem_base + QAREA0 * 16, cs_area = q_area + QCH * 16;
 #pragma unroll
     for (int n = 0; n < QCH / 64 / G; ++n) {          // 32*CPR/64 instructions per wave
       const int c = wave_s + n * G;
@@ -427,9 +435,11 @@ __global__ __launch_bounds__(G * 64, 2) void k_attn_bf16(
             (__attribute__((address_space(3))) void*)(uintptr_t)(cs_area + c * 1024), 16, 0, 0);
       }
     }
-    __builtin_amdgcn_s_waitcnt(0x0f70);
+#pragma unroll
+    for (int s = 0; s < NK0; ++s) stage_k(s);
+    wait_slots(std::integral_constant<int, NK0>{}, min(NK0, n_steps));   // Q tile and table have landed
     __syncthreads();
-    const uint4* q_lds = &smem[0][0][0];
+    const uint4* q_lds = &smem[QAREA0];
     const uint4* cs_lds = q_lds + QCH;
     auto swz = [](int L) { const int R = L >> 4, pos = L & 15; return (R << 4) + (pos ^ (R & 15)); };
     float x[KT][8];
@@ -467,105 +477,114 @@ __global__ __launch_bounds__(G * 64, 2) void k_attn_bf16(
       pk.w = pack_bf16(x[t][6] * f, x[t][7] * f);
       qf[t] = as_bf16x8(pk);
     }
-    __syncthreads();                                  // the stage memory may now be overwritten
+    __syncthreads();                                  // the area may now be overwritten
   }
 
   // ---- pipeline prologue: P(0), S(1), K operand of step 2, V operand of step 0
 #pragma unroll
-  for (int j = 0; j < NS; ++j) stage(j, j);
-  __builtin_amdgcn_s_waitcnt(0x0f70);
+  for (int s = NK0; s < NS; ++s) stage_k(s);
+#pragma unroll
+  for (int s = 0; s < NS; ++s) stage_v(s);
+  // K of the first steps (staged before the Q tile) must have landed; what was issued just now
+  // may still be in flight
+  if constexpr (NK0 >= 2)
+    wait_slots(std::integral_constant<int, 2 * NS - NK0>{},
+               min(NS, n_steps) + min(max(n_steps - NK0, 0), NS - NK0));
+  else
+    __builtin_amdgcn_s_waitcnt(0x0f70);
   __syncthreads();
-  const int last = n_steps - 1;
+  f32x16 sA, sB;           // score tiles, alternating roles from step to step
+  unsigned pA[8], pB[8];   // probability tiles (bf16 pairs), likewise
   load_k(0);
   wait_kv();
-  f32x16 s0 = qk();
+  qk(sA);                                            // S(0)
   __builtin_amdgcn_sched_barrier(0);
-  load_k(min(1, last));
-  if (0 >= tile.n_full * 64) apply_mask(s0, step_key0(0));
-  unsigned p0[8];
-  float rs0 = probs(s0, p0);
+  load_k(min(1, last) % NS);
+  if (0 >= tile.n_full * 64) apply_mask(sA, step_key0(0));
+  float rs0 = probs(sA, pA);
   wait_kv();
-  f32x16 s1 = qk();
+  qk(sB);                                            // S(1)
   __builtin_amdgcn_sched_barrier(0);
+  // Everything staged so far is needed from here on, and every wave is done with K slots 0 and 1:
+  // refill them (steps NS, NS+1).  From now on iteration j issues K(j+2+NS) and V^T(j+NS).
+  __builtin_amdgcn_s_waitcnt(0x0f70);
+  __syncthreads();
+  stage_k(NS);
+  stage_k(NS + 1);
   {   // same issue order as inside the loop: V^T t, K t, V^T t+1, ...
-    const unsigned sbk = (unsigned)(min(2, last) % NS) * STAGE_BYTES;
+    const unsigned sbk = (unsigned)(min(2, last) % NS) * SLOT_BYTES;
     static_for<0, KT>([&](auto t) {
       constexpr int uu = decltype(t)::value / DB, db = decltype(t)::value % DB;
       vf[uu][db] = lds_read_b128<(uu * 2 * D + db * 32) * 16>(v_off);
-      kf[t] = lds_read_b128<0>(k_off[t] + sbk);
+      kf[t] = lds_read_b128<decltype(t)::value * 1024>(k_off + sbk);
     });
   }
-  if (out_of_window(rs0)) rs0 = recentre(s0, s1, p0);
+  if (out_of_window(rs0)) rs0 = recentre(sA, sB, pA);
   l_run += rs0;
-  // LDS stage of step j+1 (b1), of step j+3 (b3) and the stage freed by step j (bs = j % NS)
-  int b1 = min(1, last) % NS, b3 = min(3, last) % NS, bs = 0;
 
-  for (int j = 0; j < n_steps; ++j) {
-    // The operands of this iteration are in registers once the LDS reads land; after the barrier
-    // stage j % NS is free and steps <= j+3 must be visible: up to NS-4 newer stages in flight.
-    // only the last read of the previous block (a K operand) may still be outstanding: the V^T
-    // reads of step j have left the stage that is refilled after the barrier
-    asm volatile("s_waitcnt lgkmcnt(1)" ::: "memory");
+  // One step: O^T += V^T P^T of step j and S^T of step j+2 on the MFMA pipe, the probabilities of
+  // step j+1 on the VALU, and the LDS reads of the next step's operands (V^T of step j+1, K of
+  // step j+3), each issued as soon as the register it refills has been consumed.
+  //   s_in  scores of step j+1 (input)          s_out  scores of step j+2 (result)
+  //   p_in  probabilities of step j (input)     p_out  probabilities of step j+1 (result)
+  int slot_v = min(1, last) % NS, slot_k = min(3, last) % NS;   // slots of step j+1 and step j+3
+  auto step = [&](int j, f32x16& s_in, f32x16& s_out, unsigned (&p_in)[8], unsigned (&p_out)[8],
+                  auto last_of_pair) {
+    // All operand reads of the previous step have landed: its V^T slot (step j) and K slot (step
+    // j+2) can be refilled once every wave is here.  Steps up to j+3 (K) and j+1 (V^T) must be
+    // visible; everything issued after them may stay in flight:
+    //   K(j+4) .. K(j+1+NS) and V^T(j+2) .. V^T(j+NS-1), as far as they exist and were issued.
+    wait_kv();
     {
-      const int newer = min(j + NS - 1, last) - (j + 3);
-      if (newer >= NS - 4 && NS > 4) __builtin_amdgcn_s_waitcnt(vmcnt_imm((NS - 4) * LPS));
-      else __builtin_amdgcn_s_waitcnt(0x0f70);
+      const int cnt_k = min(NS - 2, j + 2), cnt_v = min(NS - 2, j);
+      const int none_k = min(max(j + 1 + NS - last, 0), cnt_k);
+      const int none_v = min(max(j + NS - 1 - last, 0), cnt_v);
+      wait_slots(std::integral_constant<int, 2 * NS - 4>{}, cnt_k - none_k + cnt_v - none_v);
     }
     __builtin_amdgcn_s_barrier();
-    stage(j + NS, bs);
-    const bool have1 = j + 1 <= last;
+    stage_k(j + 2 + NS);
+    stage_v(j + NS);
+    const bool have1 = !decltype(last_of_pair)::value || j + 1 <= last;
     if (have1) {
       const int key0 = step_key0(j + 1);
-      if (key0 >= tile.n_full * 64) apply_mask(s1, key0);
+      if (key0 >= tile.n_full * 64) apply_mask(s_in, key0);
     }
     __builtin_amdgcn_sched_barrier(0);
 
-    // ---- one fused block: O^T += V^T P^T of step j and S^T of step j+2 on the MFMA pipe, the
-    // probabilities of step j+1 on the VALU, and the LDS reads of the next iteration's operands
-    // (V^T of step j+1, K of step j+3), each issued as soon as the register it refills has been
-    // consumed.  LDS reads complete in order and 2 KT are issued per iteration, so an operand read
-    // one iteration ago is valid once at most 2 KT - 1 younger reads are outstanding.
-    asm volatile("" : "+v"(cinit));
-    f32x16 s2 = cinit;
-    const bf16x8 pfa = as_bf16x8(make_uint4(p0[0], p0[1], p0[2], p0[3]));
-    const bf16x8 pfb = as_bf16x8(make_uint4(p0[4], p0[5], p0[6], p0[7]));
-    unsigned p1[8];
-    float rs1 = 0.0f;
-    const unsigned sb1 = (unsigned)b1 * STAGE_BYTES, sb3 = (unsigned)b3 * STAGE_BYTES;
+    const bf16x8 pfa = as_bf16x8(make_uint4(p_in[0], p_in[1], p_in[2], p_in[3]));
+    const bf16x8 pfb = as_bf16x8(make_uint4(p_in[4], p_in[5], p_in[6], p_in[7]));
+    float rs = 0.0f;
+    const unsigned sbv = (unsigned)slot_v * SLOT_BYTES, sbk = (unsigned)slot_k * SLOT_BYTES;
     static_for<0, KT>([&](auto t) {
       constexpr int uu = decltype(t)::value / DB, db = decltype(t)::value % DB;
-      if constexpr (KT == 8) asm volatile("s_waitcnt lgkmcnt(15)" : "+v"(vf[uu][db]));
-      else asm volatile("s_waitcnt lgkmcnt(7)" : "+v"(vf[uu][db]));
       o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[uu][db], uu ? pfb : pfa, o[db], 0, 0, 0);
-      vf[uu][db] = lds_read_b128<(uu * 2 * D + db * 32) * 16>(v_off + sb1);
-      if constexpr (KT == 8) asm volatile("s_waitcnt lgkmcnt(15)" : "+v"(kf[t]));
-      else asm volatile("s_waitcnt lgkmcnt(7)" : "+v"(kf[t]));
-      s2 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[t], qf[t], s2, 0, 0, 0);
-      kf[t] = lds_read_b128<0>(k_off[t] + sb3);
+      vf[uu][db] = lds_read_b128<(uu * 2 * D + db * 32) * 16>(v_off + sbv);
+      if constexpr (decltype(t)::value == 0) qk_first(s_out);
+      else s_out = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[t], qf[t], s_out, 0, 0, 0);
+      kf[t] = lds_read_b128<decltype(t)::value * 1024>(k_off + sbk);
       constexpr int PAIRS = 8 / KT;                   // probability pairs formed per k-step
 #pragma unroll
       for (int e = decltype(t)::value * PAIRS; e < (decltype(t)::value + 1) * PAIRS; ++e) {
-        p1[e] = pack_bf16(prob(s1[2 * e]), prob(s1[2 * e + 1]));
-        rs1 = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, p1[e]),
-                                              __builtin_bit_cast(bf16x2, 0x3f803f80u), rs1, false);
+        p_out[e] = pack_bf16(prob(s_in[2 * e]), prob(s_in[2 * e + 1]));
+        rs = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, p_out[e]),
+                                             __builtin_bit_cast(bf16x2, 0x3f803f80u), rs, false);
       }
     });
+    asm volatile("" : "+v"(rs));                      // the row sum belongs to this block
     __builtin_amdgcn_sched_barrier(0);
     if (have1) {
-      if (out_of_window(rs1)) rs1 = recentre(s1, s2, p1);
-      l_run += rs1;
+      if (out_of_window(rs)) rs = recentre(s_in, s_out, p_out);
+      l_run += rs;
     }
-    s1 = s2;
-#pragma unroll
-    for (int e = 0; e < 8; ++e) p0[e] = p1[e];
-    bs = bs + 1 == NS ? 0 : bs + 1;
-    b1 = (j + 2 <= last) ? (b1 + 1 == NS ? 0 : b1 + 1) : b1;
-    b3 = (j + 4 <= last) ? (b3 + 1 == NS ? 0 : b3 + 1) : b3;
+    slot_v = (j + 2 <= last) ? (slot_v + 1 == NS ? 0 : slot_v + 1) : slot_v;
+    slot_k = (j + 4 <= last) ? (slot_k + 1 == NS ? 0 : slot_k + 1) : slot_k;
+  };
+  for (int j = 0; j < n_steps; j += 2) {
+    step(j, sB, sA, pA, pB, std::false_type{});
+    step(j + 1, sA, sB, pB, pA, std::true_type{});
   }
   wait_kv();
 
-#undef sK
-#undef sV
   // ---- epilogue: normalise, then transpose through LDS so that every output row leaves as one
   // contiguous run (2 D bytes in bf16; fp32 goes in two halves of D/2 features to bound the area)
   const float l_tot = pair_sum(l_run);
@@ -581,7 +600,7 @@ __global__ __launch_bounds__(G * 64, 2) void k_attn_bf16(
       return cnt > PV_SHORT_ROW_KEYS;
     };
     constexpr int RS = 2 * D + 16;                    // row stride: 16 B of padding spreads the banks
-    char* tr = reinterpret_cast<char*>(&smem[0][0][0]) + (size_t)wave * (32 * RS);
+    char* tr = reinterpret_cast<char*>(&smem[0]) + (size_t)wave * (32 * RS);
     if (out_f32) {
       float* op = reinterpret_cast<float*>(out);
 #pragma unroll
@@ -686,20 +705,8 @@ hipError_t launch_attn_bf16(const int32_t* plan_dev, const PlanHeader& h, const 
   const float qscale = scale * 1.4426950408889634f;
   const bool out_f32 = out_dtype == PV_F32;
   if (ev0) { e = hipEventRecord(ev0, s); if (e != hipSuccess) return e; }
-  // Default: the generic kernel (32 query rows per wave, two workgroups per CU).  The variant with
-  // 64 query rows per wave is selected with PV_ATTN_KERNEL=m64 (A/B measurements); it halves the
-  // LDS operand traffic but runs one workgroup per CU and currently loses more to the exposed
-  // per-item prologue than it gains.
-  static const bool use_m64 = [] {
-    const char* v = std::getenv("PV_ATTN_KERNEL");
-    return v && std::strcmp(v, "m64") == 0;
-  }();
-  e = !use_m64 ? hipErrorNotSupported
-                    : launch_attn_m64(plan_dev, h, kq, krot, vt, cs, out, lse, hq, hkv, d, qscale, rope, out_f32, s);
-  if (e == hipErrorNotSupported) {
-    if (d == 64) e = dispatch_g<64>(hq / hkv, plan_dev, h, kq, krot, vt, cs, out, lse, hq, hkv, qscale, rope, out_f32, s);
-    else e = dispatch_g<128>(hq / hkv, plan_dev, h, kq, krot, vt, cs, out, lse, hq, hkv, qscale, rope, out_f32, s);
-  }
+  if (d == 64) e = dispatch_g<64>(hq / hkv, plan_dev, h, kq, krot, vt, cs, out, lse, hq, hkv, qscale, rope, out_f32, s);
+  else e = dispatch_g<128>(hq / hkv, plan_dev, h, kq, krot, vt, cs, out, lse, hq, hkv, qscale, rope, out_f32, s);
   if (e != hipSuccess) return e;
   if (ev1) { e = hipEventRecord(ev1, s); if (e != hipSuccess) return e; }
   return hipSuccess;

@@ -55,12 +55,5 @@ __device__ __forceinline__ void static_for(F&& f) {
 // s_waitcnt immediate (gfx9 encoding) that waits for vmcnt <= n only.
 __host__ __device__ constexpr int vmcnt_imm(int n) { return 0x0f70 | (n & 15) | ((n >> 4) << 14); }
 
-// Launcher of the kernel with 64 query rows per wave (one wave per SIMD); returns
-// hipErrorNotSupported for shapes it does not cover (the caller then uses the generic kernel).
-hipError_t launch_attn_m64(const int32_t* plan, const PlanHeader& h, const uint16_t* q,
-                           const uint16_t* krot, const uint16_t* vt, const float2* cs, void* out,
-                           float* lse, int hq, int hkv, int d, float qscale, bool rope,
-                           bool out_f32, hipStream_t s);
-
 }  // namespace pv
 #endif
