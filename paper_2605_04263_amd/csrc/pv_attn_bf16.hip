@@ -264,14 +264,14 @@ __global__ __launch_bounds__(G * 64, 2) __attribute__((amdgpu_waves_per_eu(2))) 
           (__attribute__((address_space(3))) void*)(uintptr_t)(lds0 + c * 1024), 16, 0, 0);
     }
   };
-  auto stage_k = [&](int s) {
-    if (s > last) return;
-    stage_slot(krot_b + (int64_t)step_key0(s) * (D * 2), smem_base + (unsigned)(s % NS) * SLOT_BYTES);
+  auto stage_k_to = [&](int s, int slot) {             // step s (<= last) into K slot `slot`
+    stage_slot(krot_b + (int64_t)step_key0(s) * (D * 2), smem_base + (unsigned)slot * SLOT_BYTES);
   };
-  auto stage_v = [&](int s) {
-    if (s > last) return;
-    stage_slot(vt_b + (int64_t)step_key0(s) * (D * 2), vring + (unsigned)(s % NS) * SLOT_BYTES);
+  auto stage_v_to = [&](int s, int slot) {
+    stage_slot(vt_b + (int64_t)step_key0(s) * (D * 2), vring + (unsigned)slot * SLOT_BYTES);
   };
+  auto stage_k = [&](int s) { if (s <= last) stage_k_to(s, s % NS); };
+  auto stage_v = [&](int s) { if (s <= last) stage_v_to(s, s % NS); };
   // wait until at most n slots' worth of this wave's staging loads are outstanding (every wave
   // issues at least HPW loads per slot, so n * HPW never exceeds what is really in flight)
   auto wait_slots = [&](auto max_n, int n) {           // n <= max_n
@@ -312,31 +312,19 @@ __global__ __launch_bounds__(G * 64, 2) __attribute__((amdgpu_waves_per_eu(2))) 
   for (int db = 0; db < DB; ++db)
 #pragma unroll
     for (int r = 0; r < 16; ++r) o[db][r] = 0.0f;
-  // Scores are accumulated on top of cinit = -mref, so the MFMA result is already s - mref and the
-  // probability is a bare exp2.  mref is only re-centred when a row sum leaves a safe window (see
-  // recentre below); l_run and o are relative to mref.
-  float mref = 0.0f, l_run = 0.0f;          // mref in score units (log2 units when FOLD)
-  const float esc = FOLD ? 1.0f : qscale;   // exponent scale: p = 2^(esc * (s - mref))
-  auto prob = [&](float x) { return __builtin_amdgcn_exp2f(FOLD ? x : x * esc); };
-  f32x16 cinit;
-#pragma unroll
-  for (int r = 0; r < 16; ++r) cinit[r] = 0.0f;
-
-  // First product of a score tile: accumulates on cinit but writes other registers, so that no
-  // copy of cinit is needed (the compiler's own form ties the result to the accumulator input).
-  // The instruction is opaque to the compiler's hazard handling.  Its inputs are written long
-  // before (LDS reads behind a wait, Q and cinit outside the block).  Its result must not be
-  // touched by a non-MFMA instruction for 8 passes + 3 wait states; normally the next product
-  // consumes it, but the register allocator may place a copy there (it does when the accumulators
-  // live in AGPRs), so the wait states are part of the statement.
-  auto qk_first = [&](f32x16& acc) {
-    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %3\n\ts_nop 7\n\ts_nop 7"
-                 : "=&v"(acc) : "v"(kf[0]), "v"(qf[0]), "v"(cinit));
+  // The probability of a score s is 2^(esc * s - mref): mref, in log2 units, is a per-row reference
+  // that is only re-centred when a row sum leaves a safe window (see recentre below); l_run and o
+  // are relative to it.  nmref = -mref is what the exponent adds.
+  float nmref = 0.0f, l_run = 0.0f;
+  const float esc = FOLD ? 1.0f : qscale;   // FOLD: the scale is already in Q
+  auto prob = [&](float x) {
+    return __builtin_amdgcn_exp2f(FOLD ? x + nmref : __builtin_fmaf(x, esc, nmref));
   };
   auto qk = [&](f32x16& acc) {
-    qk_first(acc);
 #pragma unroll
-    for (int t = 1; t < KT; ++t) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[t], qf[t], acc, 0, 0, 0);
+    for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
+#pragma unroll
+    for (int t = 0; t < KT; ++t) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[t], qf[t], acc, 0, 0, 0);
   };
   auto apply_mask = [&](f32x16& sc, int key0) {
 #pragma unroll
@@ -365,29 +353,26 @@ __global__ __launch_bounds__(G * 64, 2) __attribute__((amdgpu_waves_per_eu(2))) 
   // [2^-40, 2^40] (also catches inf/NaN/0).  Rare: first steps of a row, masked steps with no
   // visible key, or scores drifting by more than 40 octaves.  The reference moves to this step's
   // row maximum, but never so far down that the history (l, O) would leave fp32 range:
-  // delta >= log2(l) - 20.  `sc` are the scores being exponentiated, `sn` the scores already
-  // accumulated for the following step with the old reference.  Both half-waves of a row take
-  // identical decisions.
-  auto recentre = [&](f32x16& sc, f32x16& sn, unsigned (&pw)[8]) {
+  // mref_new >= mref + log2(l) - 20.  `sc` are the scores being exponentiated.  Both half-waves of
+  // a row take identical decisions.
+  auto recentre = [&](const f32x16& sc, unsigned (&pw)[8]) {
     float mx = sc[0];
 #pragma unroll
     for (int r = 1; r < 16; ++r) mx = fmaxf(mx, sc[r]);
     mx = pair_max(mx);
     const float l_tot = pair_sum(l_run);
     if (mx > -INFINITY && mx < INFINITY) {      // rows with no visible key keep their reference
-      float delta = mx, alpha = 0.0f;           // empty history: nothing to rescale
+      float nm_new = -mx * esc, alpha = 0.0f;   // empty history: nothing to rescale
       if (l_tot > 0.0f) {
-        delta = fmaxf(mx, (__builtin_amdgcn_logf(l_tot) - 20.0f) / esc);
-        alpha = __builtin_amdgcn_exp2f(-delta * esc);
+        nm_new = fminf(nm_new, nmref - (__builtin_amdgcn_logf(l_tot) - 20.0f));
+        alpha = __builtin_amdgcn_exp2f(nm_new - nmref);
       }
-      mref += delta;
+      nmref = nm_new;
       l_run *= alpha;
 #pragma unroll
       for (int db = 0; db < DB; ++db)
 #pragma unroll
         for (int r = 0; r < 16; ++r) o[db][r] *= alpha;
-#pragma unroll
-      for (int r = 0; r < 16; ++r) { sc[r] -= delta; sn[r] -= delta; cinit[r] = -mref; }
     }
     return probs(sc, pw);
   };
@@ -438,7 +423,7 @@ __global__ __launch_bounds__(G * 64, 2) __attribute__((amdgpu_waves_per_eu(2))) 
 #pragma unroll
     for (int s = 0; s < NK0; ++s) stage_k(s);
     wait_slots(std::integral_constant<int, NK0>{}, min(NK0, n_steps));   // Q tile and table have landed
-    __syncthreads();
+    __builtin_amdgcn_s_barrier();
     const uint4* q_lds = &smem[QAREA0];
     const uint4* cs_lds = q_lds + QCH;
     auto swz = [](int L) { const int R = L >> 4, pos = L & 15; return (R << 4) + (pos ^ (R & 15)); };
@@ -492,7 +477,7 @@ __global__ __launch_bounds__(G * 64, 2) __attribute__((amdgpu_waves_per_eu(2))) 
                min(NS, n_steps) + min(max(n_steps - NK0, 0), NS - NK0));
   else
     __builtin_amdgcn_s_waitcnt(0x0f70);
-  __syncthreads();
+  __builtin_amdgcn_s_barrier();        // not __syncthreads(): that would wait for the loads in flight
   f32x16 sA, sB;           // score tiles, alternating roles from step to step
   unsigned pA[8], pB[8];   // probability tiles (bf16 pairs), likewise
   load_k(0);
@@ -519,7 +504,7 @@ __global__ __launch_bounds__(G * 64, 2) __attribute__((amdgpu_waves_per_eu(2))) 
       kf[t] = lds_read_b128<decltype(t)::value * 1024>(k_off + sbk);
     });
   }
-  if (out_of_window(rs0)) rs0 = recentre(sA, sB, pA);
+  if (out_of_window(rs0)) rs0 = recentre(sA, pA);
   l_run += rs0;
 
   // One step: O^T += V^T P^T of step j and S^T of step j+2 on the MFMA pipe, the probabilities of
@@ -528,22 +513,31 @@ __global__ __launch_bounds__(G * 64, 2) __attribute__((amdgpu_waves_per_eu(2))) 
   //   s_in  scores of step j+1 (input)          s_out  scores of step j+2 (result)
   //   p_in  probabilities of step j (input)     p_out  probabilities of step j+1 (result)
   int slot_v = min(1, last) % NS, slot_k = min(3, last) % NS;   // slots of step j+1 and step j+3
+  //   steady: both refills of this step exist and the pipeline is full, so the wait is a constant
+  //           and the refills are issued from inside the MFMA block (no branch splits the block)
+  int sj = 0;                                           // j % NS
   auto step = [&](int j, f32x16& s_in, f32x16& s_out, unsigned (&p_in)[8], unsigned (&p_out)[8],
-                  auto last_of_pair) {
+                  auto last_of_pair, auto steady) {
+    constexpr bool STEADY = decltype(steady)::value;
     // All operand reads of the previous step have landed: its V^T slot (step j) and K slot (step
     // j+2) can be refilled once every wave is here.  Steps up to j+3 (K) and j+1 (V^T) must be
     // visible; everything issued after them may stay in flight:
     //   K(j+4) .. K(j+1+NS) and V^T(j+2) .. V^T(j+NS-1), as far as they exist and were issued.
     wait_kv();
-    {
+    if constexpr (STEADY && (2 * NS - 4) * HPW <= 63) {
+      __builtin_amdgcn_s_waitcnt(vmcnt_imm((2 * NS - 4) * HPW));
+    } else {
       const int cnt_k = min(NS - 2, j + 2), cnt_v = min(NS - 2, j);
       const int none_k = min(max(j + 1 + NS - last, 0), cnt_k);
       const int none_v = min(max(j + NS - 1 - last, 0), cnt_v);
       wait_slots(std::integral_constant<int, 2 * NS - 4>{}, cnt_k - none_k + cnt_v - none_v);
     }
     __builtin_amdgcn_s_barrier();
-    stage_k(j + 2 + NS);
-    stage_v(j + NS);
+    const int slot_ks = sj + 2 >= NS ? sj + 2 - NS : sj + 2;   // (j + 2) % NS
+    if constexpr (!STEADY) {
+      if (j + 2 + NS <= last) stage_k_to(j + 2 + NS, slot_ks);
+      if (j + NS <= last) stage_v_to(j + NS, sj);
+    }
     const bool have1 = !decltype(last_of_pair)::value || j + 1 <= last;
     if (have1) {
       const int key0 = step_key0(j + 1);
@@ -555,33 +549,86 @@ __global__ __launch_bounds__(G * 64, 2) __attribute__((amdgpu_waves_per_eu(2))) 
     const bf16x8 pfb = as_bf16x8(make_uint4(p_in[4], p_in[5], p_in[6], p_in[7]));
     float rs = 0.0f;
     const unsigned sbv = (unsigned)slot_v * SLOT_BYTES, sbk = (unsigned)slot_k * SLOT_BYTES;
+    // The block is 2 KT groups of one MFMA, one operand refill and a share of the VALU work, and
+    // the issue order is fixed group by group.  (Left to itself the scheduler clusters the MFMAs,
+    // and the VALU work then runs while the matrix pipe idles.)  The wave issues in order, so a
+    // VALU instruction waiting for its input also holds back the next MFMA: the softmax work of
+    // score i is therefore spread over consecutive groups,
+    //   exponent argument -> exp2 -> (pair) bf16 pack -> (pair) row-sum dot,
+    // each stage one group after the stage it depends on.
+    constexpr int NG = 2 * KT, SPG = 16 / NG;          // groups, scores per group
+    float ea[16], ex[16];                              // exponent arguments, exponentials
+    auto v_arg = [&](auto i) {
+      constexpr int I = decltype(i)::value;
+      if constexpr (I < 16) ea[I] = FOLD ? s_in[I] + nmref : __builtin_fmaf(s_in[I], esc, nmref);
+    };
+    auto v_exp = [&](auto i) {
+      constexpr int I = decltype(i)::value;
+      if constexpr (I < 16) ex[I] = __builtin_amdgcn_exp2f(ea[I]);
+    };
+    auto valu_group = [&](auto g) {                    // the VALU share of group g (g = -1: before)
+      constexpr int GI = decltype(g)::value;
+      static_for<0, SPG>([&](auto k) {
+        constexpr int I = (GI + 1) * SPG + decltype(k)::value;   // exp2 runs one group ahead
+        v_exp(std::integral_constant<int, I>{});
+        v_arg(std::integral_constant<int, I + SPG>{});
+      });
+      static_for<0, 8>([&](auto e) {
+        constexpr int E = decltype(e)::value;
+        constexpr int GC = (2 * E + 1) / SPG;            // group after the pair's second exp2
+        if constexpr (GC == GI) p_out[E] = pack_bf16(ex[2 * E], ex[2 * E + 1]);
+        if constexpr (GC + 1 == GI)
+          rs = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, p_out[E]),
+                                               __builtin_bit_cast(bf16x2, 0x3f803f80u), rs, false);
+      });
+    };
+    static_for<0, SPG>([&](auto k) { v_arg(k); });
+    valu_group(std::integral_constant<int, -1>{});
+    __builtin_amdgcn_sched_barrier(0);
     static_for<0, KT>([&](auto t) {
-      constexpr int uu = decltype(t)::value / DB, db = decltype(t)::value % DB;
+      constexpr int T = decltype(t)::value;
+      constexpr int uu = T / DB, db = T % DB;
       o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[uu][db], uu ? pfb : pfa, o[db], 0, 0, 0);
-      vf[uu][db] = lds_read_b128<(uu * 2 * D + db * 32) * 16>(v_off + sbv);
-      if constexpr (decltype(t)::value == 0) qk_first(s_out);
-      else s_out = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[t], qf[t], s_out, 0, 0, 0);
-      kf[t] = lds_read_b128<decltype(t)::value * 1024>(k_off + sbk);
-      constexpr int PAIRS = 8 / KT;                   // probability pairs formed per k-step
+      lds_refill_b128<(uu * 2 * D + db * 32) * 16>(vf[uu][db], v_off + sbv);
+      valu_group(std::integral_constant<int, 2 * T>{});
+      __builtin_amdgcn_sched_barrier(0);
+      if constexpr (T == 0) {
 #pragma unroll
-      for (int e = decltype(t)::value * PAIRS; e < (decltype(t)::value + 1) * PAIRS; ++e) {
-        p_out[e] = pack_bf16(prob(s_in[2 * e]), prob(s_in[2 * e + 1]));
-        rs = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, p_out[e]),
-                                             __builtin_bit_cast(bf16x2, 0x3f803f80u), rs, false);
+        for (int r = 0; r < 16; ++r) s_out[r] = 0.0f;   // becomes the constant-zero accumulator input
       }
+      s_out = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[t], qf[t], s_out, 0, 0, 0);
+      lds_refill_b128<T * 1024>(kf[t], k_off + sbk);
+      valu_group(std::integral_constant<int, 2 * T + 1>{});
+      if constexpr (STEADY && T == 1) stage_k_to(j + 2 + NS, slot_ks);
+      if constexpr (STEADY && T == 2) stage_v_to(j + NS, sj);
+      __builtin_amdgcn_sched_barrier(0);
     });
+    valu_group(std::integral_constant<int, NG>{});     // what is left: the last row-sum term
     asm volatile("" : "+v"(rs));                      // the row sum belongs to this block
     __builtin_amdgcn_sched_barrier(0);
     if (have1) {
-      if (out_of_window(rs)) rs = recentre(s_in, s_out, p_out);
+      if (out_of_window(rs)) rs = recentre(s_in, p_out);
       l_run += rs;
     }
     slot_v = (j + 2 <= last) ? (slot_v + 1 == NS ? 0 : slot_v + 1) : slot_v;
     slot_k = (j + 4 <= last) ? (slot_k + 1 == NS ? 0 : slot_k + 1) : slot_k;
+    sj = sj + 1 == NS ? 0 : sj + 1;
   };
-  for (int j = 0; j < n_steps; j += 2) {
-    step(j, sB, sA, pA, pB, std::false_type{});
-    step(j + 1, sA, sB, pB, pA, std::true_type{});
+  // Three loops over pairs of steps: filling the pipeline, steady state (the pipeline is full,
+  // j >= NS - 2, and step j + 1 still refills a K slot, j + 3 + NS <= last), draining.
+  constexpr int JS = (NS - 2 + 1) & ~1;
+  int j = 0;
+  for (; j < n_steps && j < JS; j += 2) {
+    step(j, sB, sA, pA, pB, std::false_type{}, std::false_type{});
+    step(j + 1, sA, sB, pB, pA, std::true_type{}, std::false_type{});
+  }
+  for (; j + 3 + NS <= last; j += 2) {
+    step(j, sB, sA, pA, pB, std::false_type{}, std::true_type{});
+    step(j + 1, sA, sB, pB, pA, std::true_type{}, std::true_type{});
+  }
+  for (; j < n_steps; j += 2) {
+    step(j, sB, sA, pA, pB, std::false_type{}, std::false_type{});
+    step(j + 1, sA, sB, pB, pA, std::true_type{}, std::false_type{});
   }
   wait_kv();
 
@@ -643,7 +690,7 @@ __global__ __launch_bounds__(G * 64, 2) __attribute__((amdgpu_waves_per_eu(2))) 
       }
     }
     if (lse && hh == 0 && valid && a_end + i_loc - b_start + 1 > PV_SHORT_ROW_KEYS)
-      lse[(int64_t)head * h.total_tokens + g] = (mref * esc + log2f(l_tot)) * 0.6931471805599453f;
+      lse[(int64_t)head * h.total_tokens + g] = (log2f(l_tot) - nmref) * 0.6931471805599453f;
   }
 }
 

@@ -44,6 +44,12 @@ __device__ __forceinline__ bf16x8 lds_read_b128(unsigned addr) {
   asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(r) : "v"(addr), "n"(OFF));
   return r;
 }
+// The same read refilling `r` in place: the result is tied to the register that held the operand
+// just consumed, so the allocator cannot spread a double-buffered operand over two register sets.
+template <int OFF>
+__device__ __forceinline__ void lds_refill_b128(bf16x8& r, unsigned addr) {
+  asm volatile("ds_read_b128 %0, %1 offset:%2" : "+v"(r) : "v"(addr), "n"(OFF));
+}
 template <int I, int N, typename F>
 __device__ __forceinline__ void static_for(F&& f) {
   if constexpr (I < N) {
