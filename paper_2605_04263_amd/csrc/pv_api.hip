@@ -265,9 +265,8 @@ pv_status pv_build_mask(const pv_problem* problem, const pv_sizes* sizes, void* 
   st = arch_ok_cached();
   if (st != PV_OK) return st;
   hipStream_t s = (hipStream_t)stream;
-  hipError_t e = launch_upload((int32_t*)plan_dev, img.data(), (int)img.size(), s);
-  if (e != hipSuccess) return hip_fail(e);
-  e = launch_plan_kernels((int32_t*)plan_dev, h, dense_mask_dev, s);
+  hipError_t e = launch_plan_kernels((int32_t*)plan_dev, h, img.data(), (int)img.size(),
+                                     dense_mask_dev, s);
   if (e != hipSuccess) return hip_fail(e);
   return PV_OK;
 }

@@ -1,10 +1,10 @@
 // bf16 MFMA path of pv_masked_attention for gfx950.
 //
-// Three launches on the caller's stream:
-//   k_rope_table_bf16  cos/sin of every token's rotary angle (fp64 angle, fp32 result)
-//   k_prep_kv          K rotated and written head-major in key tiles; V written transposed in
-//                      16-key slabs whose element order is the MFMA operand order, so the main
-//                      kernel stages both with plain 16-byte copies
+// Two launches on the caller's stream:
+//   k_prep_kv          cos/sin of every token's rotary angle (fp64 angle, fp32 result), K rotated
+//                      and written head-major in MFMA operand order, V written transposed in 16-key
+//                      slabs in MFMA operand order, so the main kernel stages both with plain
+//                      16-byte copies; extra blocks evaluate the rows with very few keys in fp32
 //   k_attn_bf16        flash-style fused Q K^T / online softmax / P V.  One workgroup = one query
 //                      tile (32 tokens) x one kv head; wave w owns query head kvh*G + w, so the
 //                      G query heads of a GQA group share every K/V tile staged in LDS.
@@ -18,21 +18,7 @@
 
 namespace pv {
 
-// ---------------------------------------------------------------- rotary table
-__global__ __launch_bounds__(256) void k_rope_table_bf16(const int32_t* plan, PlanHeader h,
-                                                         RopeFreq f, int half, float2* cs) {
-  const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (idx >= (int64_t)h.total_tokens * half) return;
-  const int g = (int)(idx / half), c = (int)(idx % half);
-  const double phi = (double)plan[h.off_pos + g] * f.inv_freq[c];
-  double sn, cn;
-  sincos(phi, &sn, &cn);
-  cs[idx] = make_float2((float)cn, (float)sn);
-}
-
 // ---------------------------------------------------------------- K/V preparation
-// grid = (padded_keys / 64, Hkv), 256 threads.  Pad rows (beyond the request) are written as 0 so
-// that masked probabilities (exactly 0) never meet a non-finite value.
 struct ShortRowArgs {          // what the fp32 evaluation of the short rows needs beyond k, v, cs
   const uint16_t* q;
   void* out;
@@ -47,7 +33,7 @@ struct ShortRowArgs {          // what the fp32 evaluation of the short rows nee
 template <int D>
 __device__ void short_row(const int32_t* __restrict__ plan, const PlanHeader& h,
                           const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
-                          const float2* __restrict__ cs, int hkv, bool rope, const ShortRowArgs& a,
+                          const RopeFreq& f, int hkv, bool rope, const ShortRowArgs& a,
                           int g, int head, int lane) {
   constexpr int HALF = D / 2;
   const int kvh = head / (a.hq / hkv);
@@ -61,9 +47,11 @@ __device__ void short_row(const int32_t* __restrict__ plan, const PlanHeader& h,
   auto load_pair = [&](const uint16_t* row, int tok, float* lo_out, float* hi_out) {
     const float xl = __uint_as_float((unsigned)row[c] << 16), xh = __uint_as_float((unsigned)row[c + HALF] << 16);
     if (rope) {
-      const float2 t = cs[(int64_t)tok * HALF + c];
-      *lo_out = xl * t.x - xh * t.y;
-      *hi_out = xh * t.x + xl * t.y;
+      double sn, cn;
+      sincos((double)plan[h.off_pos + tok] * f.inv_freq[c], &sn, &cn);
+      const float tc = (float)cn, ts2 = (float)sn;
+      *lo_out = xl * tc - xh * ts2;
+      *hi_out = xh * tc + xl * ts2;
     } else { *lo_out = xl; *hi_out = xh; }
   };
   float ql, qh;
@@ -115,81 +103,117 @@ __device__ void short_row(const int32_t* __restrict__ plan, const PlanHeader& h,
   }
 }
 
+// grid = padded_keys / 16 blocks of 16 keys (all kv heads each), then one block per (short row,
+// kv head).  Pad rows (beyond the request) are written as 0 so that masked probabilities (exactly
+// 0) never meet a non-finite value.
 template <int D>
 __global__ __launch_bounds__(256) void k_prep_kv(const int32_t* __restrict__ plan, PlanHeader h,
                                                  const uint16_t* __restrict__ k,
-                                                 const uint16_t* __restrict__ v,
-                                                 const float2* __restrict__ cs, int hkv, bool rope,
+                                                 const uint16_t* __restrict__ v, RopeFreq f,
+                                                 float2* __restrict__ cs, int hkv, bool rope,
                                                  uint16_t* __restrict__ krot,
                                                  uint16_t* __restrict__ vt, ShortRowArgs sr) {
   constexpr int HALF = D / 2;
-  if ((int)blockIdx.x >= h.padded_keys / 64) {           // extra blocks: one short row each
-    const int g = plan[h.off_short + ((int)blockIdx.x - h.padded_keys / 64)];
+  constexpr int KB = 16;                       // keys per block
+  constexpr int HG = 8;                        // kv heads handled per pass
+  const int n_main = h.padded_keys / KB;
+  if ((int)blockIdx.x >= n_main) {             // extra blocks: one (short row, kv head) each
+    const int idx = (int)blockIdx.x - n_main;
+    const int g = plan[h.off_short + idx / hkv], kvh = idx % hkv;
     const int G = sr.hq / hkv;
     for (int hl = threadIdx.x >> 6; hl < G; hl += 4)
-      short_row<D>(plan, h, k, v, cs, hkv, rope, sr, g, blockIdx.y * G + hl, threadIdx.x & 63);
+      short_row<D>(plan, h, k, v, f, hkv, rope, sr, g, kvh * G + hl, threadIdx.x & 63);
     return;
   }
-  const int tile_row = blockIdx.x * 64;      // first padded key row of this tile
-  const int kvh = blockIdx.y;
-  // owner request of the tile
+  __shared__ float2 cs_s[KB][HALF];            // cos/sin of the block's tokens
+  __shared__ uint4 v_s[HG][KB][D / 8 + 1];     // V rows of one pass, padded
+  const int row0 = blockIdx.x * KB;            // first padded key row of this block
+  // owner request of the block (requests are padded to multiples of 64 keys)
   const int32_t* kp = plan + h.off_kpad_start;
   int lo = 0, hi = h.batch;
   while (hi - lo > 1) {
     const int mid = (lo + hi) >> 1;
-    if (kp[mid] <= tile_row) lo = mid; else hi = mid;
+    if (kp[mid] <= row0) lo = mid; else hi = mid;
   }
   const int b = lo;
   const int tok_base = plan[h.off_tok_start + b];
   const int n_b = plan[h.off_tok_start + b + 1] - tok_base;
-  const int key0 = tile_row - kp[b];         // first local key of the tile
-  const int64_t out_base = ((int64_t)kvh * h.padded_keys + tile_row) * D;
+  const int key0 = row0 - kp[b];               // first local key of the block
+  const int tid = threadIdx.x;
 
-  // K: thread = (key, group of 8 rotation pairs)
-  for (int item = threadIdx.x; item < 64 * (HALF / 8); item += 256) {
-    const int key = item / (HALF / 8), c0 = (item % (HALF / 8)) * 8;
-    uint4 lo4 = make_uint4(0, 0, 0, 0), hi4 = make_uint4(0, 0, 0, 0);
-    if (key0 + key < n_b) {
-      const int64_t g = tok_base + key0 + key;
-      const uint16_t* src = k + (g * hkv + kvh) * D;
-      lo4 = *reinterpret_cast<const uint4*>(src + c0);
-      hi4 = *reinterpret_cast<const uint4*>(src + c0 + HALF);
-      if (rope) {
-        const float2* t = cs + g * HALF + c0;
-        unsigned* pl = reinterpret_cast<unsigned*>(&lo4);
-        unsigned* ph = reinterpret_cast<unsigned*>(&hi4);
+  // cos/sin of the rotary angles: fp64 angle, fp32 result, also written to the table that the
+  // main kernel rotates Q with
+  if (rope) {
+    for (int item = tid; item < KB * HALF; item += 256) {
+      const int key = item / HALF, c = item % HALF;
+      float2 t = make_float2(1.0f, 0.0f);
+      if (key0 + key < n_b) {
+        const int64_t g = tok_base + key0 + key;
+        double sn, cn;
+        sincos((double)plan[h.off_pos + g] * f.inv_freq[c], &sn, &cn);
+        t = make_float2((float)cn, (float)sn);
+        cs[g * HALF + c] = t;
+      }
+      cs_s[key][c] = t;
+    }
+  }
+  for (int h0 = 0; h0 < hkv; h0 += HG) {
+    const int nh = min(HG, hkv - h0);
+    __syncthreads();                           // cs_s ready; v_s free
+    // V rows into LDS with 16-byte loads
+    for (int item = tid; item < nh * KB * (D / 8); item += 256) {
+      const int ch = item % (D / 8), hl = (item / (D / 8)) % nh, key = item / ((D / 8) * nh);
+      uint4 w = make_uint4(0, 0, 0, 0);
+      if (key0 + key < n_b)
+        w = *reinterpret_cast<const uint4*>(v + ((int64_t)(tok_base + key0 + key) * hkv + h0 + hl) * D + ch * 8);
+      v_s[hl][key][ch] = w;
+    }
+    // K: item = (key, head, group of 8 rotation pairs); consecutive threads read consecutive
+    // 16-byte pieces of the token's K row
+    for (int item = tid; item < nh * KB * (HALF / 8); item += 256) {
+      const int c0 = (item % (HALF / 8)) * 8, hl = (item / (HALF / 8)) % nh, key = item / ((HALF / 8) * nh);
+      uint4 lo4 = make_uint4(0, 0, 0, 0), hi4 = make_uint4(0, 0, 0, 0);
+      if (key0 + key < n_b) {
+        const uint16_t* src = k + ((int64_t)(tok_base + key0 + key) * hkv + h0 + hl) * D;
+        lo4 = *reinterpret_cast<const uint4*>(src + c0);
+        hi4 = *reinterpret_cast<const uint4*>(src + c0 + HALF);
+        if (rope) {
+          const float2* t = &cs_s[key][c0];
+          unsigned* pl = reinterpret_cast<unsigned*>(&lo4);
+          unsigned* ph = reinterpret_cast<unsigned*>(&hi4);
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const float2 t0 = t[2 * e], t1 = t[2 * e + 1];
-          const float l0 = bf16_lo(pl[e]), l1 = bf16_hi(pl[e]);
-          const float h0 = bf16_lo(ph[e]), h1 = bf16_hi(ph[e]);
-          pl[e] = pack_bf16(l0 * t0.x - h0 * t0.y, l1 * t1.x - h1 * t1.y);
-          ph[e] = pack_bf16(h0 * t0.x + l0 * t0.y, h1 * t1.x + l1 * t1.y);
+          for (int e = 0; e < 4; ++e) {
+            const float2 t0 = t[2 * e], t1 = t[2 * e + 1];
+            const float l0 = bf16_lo(pl[e]), l1 = bf16_hi(pl[e]);
+            const float h0f = bf16_lo(ph[e]), h1f = bf16_hi(ph[e]);
+            pl[e] = pack_bf16(l0 * t0.x - h0f * t0.y, l1 * t1.x - h1f * t1.y);
+            ph[e] = pack_bf16(h0f * t0.x + l0 * t0.y, h1f * t1.x + l1 * t1.y);
+          }
         }
       }
+      // operand order: inside a block of 32 keys, chunk (t, hh, row) = features 16 t + 8 hh .. + 7
+      // of key `row` sits at chunk index t * 64 + hh * 32 + row
+      const int prow = row0 + key;             // padded key row
+      uint4* dst = reinterpret_cast<uint4*>(krot + ((int64_t)(h0 + hl) * h.padded_keys + (prow & ~31)) * D) + (prow & 31);
+      const int ci = c0 >> 3;                  // chunk of the low half; the high one is D/16 later
+      dst[(ci >> 1) * 64 + (ci & 1) * 32] = lo4;
+      dst[((ci + D / 16) >> 1) * 64 + ((ci + D / 16) & 1) * 32] = hi4;
     }
-    // operand order: inside a block of 32 keys, chunk (t, hh, row) = features 16 t + 8 hh .. + 7
-    // of key `row` sits at chunk index t * 64 + hh * 32 + row
-    uint4* dst = reinterpret_cast<uint4*>(krot + out_base) + (key >> 5) * (32 * D / 8) + (key & 31);
-    const int ci = c0 >> 3;                       // chunk of the low half; the high one is D/16 later
-    dst[(ci >> 1) * 64 + (ci & 1) * 32] = lo4;
-    dst[((ci + D / 16) >> 1) * 64 + ((ci + D / 16) & 1) * 32] = hi4;
-  }
-
-  // V^T: slab s (16 keys) is [2][D][8]; element (hh, d, m) is key 8*(m/4) + 4*hh + (m%4) of the
-  // slab at feature d.  Thread = one 16-byte chunk (s, hh, d).
-  for (int item = threadIdx.x; item < 4 * 2 * D; item += 256) {
-    const int d = item % D, hh = (item / D) % 2, s = item / (2 * D);
-    unsigned short e[8];
+    __syncthreads();                           // v_s filled
+    // V^T: a slab (16 keys) is [2][D][8]; element (hh, d, m) is key 8*(m/4) + 4*hh + (m%4) of the
+    // slab at feature d.  Item = one 16-byte chunk (head, hh, d).
+    constexpr int VROW = (D / 8 + 1) * 8;      // padded row length in elements
+    for (int item = tid; item < nh * 2 * D; item += 256) {
+      const int d = item % D, hh = (item / D) % 2, hl = item / (2 * D);
+      const uint16_t* vs16 = reinterpret_cast<const uint16_t*>(&v_s[hl][0][0]);
+      unsigned short e[8];
 #pragma unroll
-    for (int m = 0; m < 8; ++m) {
-      const int key = key0 + s * 16 + 8 * (m / 4) + 4 * hh + (m % 4);
-      e[m] = (key < n_b) ? v[((int64_t)(tok_base + key) * hkv + kvh) * D + d] : (unsigned short)0;
+      for (int m = 0; m < 8; ++m) e[m] = vs16[(8 * (m / 4) + 4 * hh + (m % 4)) * VROW + d];
+      uint4 o;
+      o.x = e[0] | ((unsigned)e[1] << 16); o.y = e[2] | ((unsigned)e[3] << 16);
+      o.z = e[4] | ((unsigned)e[5] << 16); o.w = e[6] | ((unsigned)e[7] << 16);
+      reinterpret_cast<uint4*>(vt + ((int64_t)(h0 + hl) * h.padded_keys + row0) * D)[hh * D + d] = o;
     }
-    uint4 o;
-    o.x = e[0] | ((unsigned)e[1] << 16); o.y = e[2] | ((unsigned)e[3] << 16);
-    o.z = e[4] | ((unsigned)e[5] << 16); o.w = e[6] | ((unsigned)e[7] << 16);
-    reinterpret_cast<uint4*>(vt + out_base)[item] = o;
   }
 }
 
@@ -734,18 +758,12 @@ hipError_t launch_attn_bf16(const int32_t* plan_dev, const PlanHeader& h, const 
   const uint16_t* kk = reinterpret_cast<const uint16_t*>(k);
   const uint16_t* kv = reinterpret_cast<const uint16_t*>(v);
   hipError_t e;
-  if (rope) {
-    const int64_t n = (int64_t)h.total_tokens * (d / 2);
-    k_rope_table_bf16<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s>>>(plan_dev, h, freq, d / 2, cs);
-    e = hipGetLastError();
-    if (e != hipSuccess) return e;
-  }
   {
-    const dim3 grid((unsigned)(h.padded_keys / 64 + h.n_short_rows), (unsigned)hkv);
+    const dim3 grid((unsigned)(h.padded_keys / 16 + h.n_short_rows * hkv));
     ShortRowArgs sr;
     sr.q = kq; sr.out = out; sr.lse = lse; sr.hq = hq; sr.scale = scale; sr.out_f32 = out_dtype == PV_F32;
-    if (d == 64) k_prep_kv<64><<<grid, dim3(256), 0, s>>>(plan_dev, h, kk, kv, cs, hkv, rope, krot, vt, sr);
-    else k_prep_kv<128><<<grid, dim3(256), 0, s>>>(plan_dev, h, kk, kv, cs, hkv, rope, krot, vt, sr);
+    if (d == 64) k_prep_kv<64><<<grid, dim3(256), 0, s>>>(plan_dev, h, kk, kv, freq, cs, hkv, rope, krot, vt, sr);
+    else k_prep_kv<128><<<grid, dim3(256), 0, s>>>(plan_dev, h, kk, kv, freq, cs, hkv, rope, krot, vt, sr);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
   }

@@ -62,9 +62,9 @@ AttnWorkspace attn_workspace_layout(int64_t total_tokens, int64_t padded_keys, i
                                     int in_dtype);
 
 // --- launchers (each returns the hipError_t of its launches) ---
-hipError_t launch_upload(int32_t* plan_dev, const int32_t* host_ints, int n, hipStream_t s);
-hipError_t launch_plan_kernels(int32_t* plan_dev, const PlanHeader& h, uint8_t* dense_mask,
-                               hipStream_t s);
+// Uploads the host image (n_img ints at the start of the plan) and builds the device part.
+hipError_t launch_plan_kernels(int32_t* plan_dev, const PlanHeader& h, const int32_t* host_ints,
+                               int n_img, uint8_t* dense_mask, hipStream_t s);
 hipError_t launch_plan_export(const int32_t* plan_dev, const PlanHeader& h, int32_t* pos,
                               int32_t* aend, int32_t* bstart, int32_t* judge, hipStream_t s);
 hipError_t launch_first_reject(const int32_t* plan_dev, const PlanHeader& h, const float* logits,

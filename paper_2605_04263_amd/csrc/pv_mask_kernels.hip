@@ -13,7 +13,7 @@ __global__ __launch_bounds__(256) void k_upload(int32_t* dst, UploadChunk c, int
   if (i < n) dst[i] = c.v[i];
 }
 
-hipError_t launch_upload(int32_t* plan_dev, const int32_t* host_ints, int n, hipStream_t s) {
+static hipError_t launch_upload(int32_t* plan_dev, const int32_t* host_ints, int n, hipStream_t s) {
   // The image travels in kernel arguments: they are captured at launch, so the host buffer can
   // be released immediately and no pageable-memory copy semantics are involved.
   for (int o = 0; o < n; o += kUploadInts) {
@@ -74,30 +74,33 @@ __device__ inline int find_owner(const int32_t* start, int n, int x) {
   return lo;
 }
 
-__global__ __launch_bounds__(256) void k_plan_tokens(int32_t* plan, PlanHeader h) {
-  const int g = blockIdx.x * blockDim.x + threadIdx.x;
+// Row g of the packed batch (and, for g < total_segments, judge row g).  `img` is where the
+// uploaded part of the plan is read from (the plan itself, or a copy in LDS).
+__device__ inline void plan_token(int32_t* plan, const int32_t* img, const PlanHeader& h, int g) {
   if (g < h.total_tokens) {
-    const int b = find_owner(plan + h.off_tok_start, h.batch, g);
-    const Req r = load_req(plan, h, b);
+    const int b = find_owner(img + h.off_tok_start, h.batch, g);
+    const Req r = load_req(img, h, b);
     int pos, ae, bs;
-    row_desc(r, g - plan[h.off_tok_start + b], &pos, &ae, &bs);
+    row_desc(r, g - img[h.off_tok_start + b], &pos, &ae, &bs);
     plan[h.off_pos + g] = pos;
     plan[h.off_aend + g] = ae;
     plan[h.off_bstart + g] = bs;
   }
   if (g < h.total_segments) {
-    const int b = find_owner(plan + h.off_seg_start, h.batch, g);
-    const Req r = load_req(plan, h, b);
-    const int k = g - plan[h.off_seg_start + b];
+    const int b = find_owner(img + h.off_seg_start, h.batch, g);
+    const Req r = load_req(img, h, b);
+    const int k = g - img[h.off_seg_start + b];
     // the verdict of segment k is read at its last token
-    plan[h.off_judge + g] = plan[h.off_tok_start + b] + r.P + r.T + (k + 1) * r.S - 1;
+    plan[h.off_judge + g] = img[h.off_tok_start + b] + r.P + r.T + (k + 1) * r.S - 1;
   }
 }
 
-// One thread per query tile: the union of its rows' visible key sets, in key-tile units.
-__global__ __launch_bounds__(256) void k_plan_tiles(int32_t* plan, PlanHeader h) {
-  const int t = blockIdx.x * blockDim.x + threadIdx.x;
-  if (t >= h.n_q_tiles) return;
+__global__ __launch_bounds__(256) void k_plan_tokens(int32_t* plan, PlanHeader h) {
+  plan_token(plan, plan, h, blockIdx.x * blockDim.x + threadIdx.x);
+}
+
+// Query tile t: the union of its rows' visible key sets, in key-tile units.
+__device__ inline QTile plan_tile(const int32_t* plan, const PlanHeader& h, int t) {
   const int b = find_owner(plan + h.off_qtile_start, h.batch, t);
   const Req r = load_req(plan, h, b);
   const int t0 = (t - plan[h.off_qtile_start + b]) * h.tile_m;
@@ -129,7 +132,43 @@ __global__ __launch_bounds__(256) void k_plan_tiles(int32_t* plan, PlanHeader h)
     q.jb0 = q.n_a; q.jb1 = q.n_a;
   }
   q.kpad_base = plan[h.off_kpad_start + b];
-  reinterpret_cast<QTile*>(plan + h.off_tiles)[t] = q;
+  return q;
+}
+
+__global__ __launch_bounds__(256) void k_plan_tiles(int32_t* plan, PlanHeader h) {
+  const int t = blockIdx.x * blockDim.x + threadIdx.x;
+  if (t < h.n_q_tiles) reinterpret_cast<QTile*>(plan + h.off_tiles)[t] = plan_tile(plan, h, t);
+}
+
+// Small problems: the whole plan in one launch of one workgroup.  The host image arrives in the
+// kernel arguments and is written first; the phases are separated by workgroup barriers.
+constexpr int kSmallTokens = 8192, kSmallTiles = 1024;
+__global__ __launch_bounds__(1024) void k_plan_small(int32_t* plan, PlanHeader h, UploadChunk c,
+                                                     int n_img) {
+  __shared__ int cost_s[kSmallTiles];
+  __shared__ int32_t img_s[kUploadInts];       // the request data is read from here, not from HBM
+  const int tid = threadIdx.x;
+  for (int i = tid; i < n_img; i += 1024) { const int32_t x = c.v[i]; plan[i] = x; img_s[i] = x; }
+  __syncthreads();
+  const int n1 = h.total_tokens > h.total_segments ? h.total_tokens : h.total_segments;
+  for (int g = tid; g < n1; g += 1024) plan_token(plan, img_s, h, g);
+  QTile mine;
+  int my_cost = 0;
+  if (tid < h.n_q_tiles) {
+    mine = plan_tile(img_s, h, tid);
+    my_cost = mine.n_a + (mine.jb1 - mine.jb0);
+    reinterpret_cast<QTile*>(plan + h.off_tiles)[tid] = mine;
+    cost_s[tid] = my_cost;
+  }
+  __syncthreads();
+  if (tid < h.n_q_tiles) {          // longest first, stable
+    int rank = 0;
+    for (int x = 0; x < h.n_q_tiles; ++x) {
+      const int cx = cost_s[x];
+      rank += (cx > my_cost) || (cx == my_cost && x < tid);
+    }
+    reinterpret_cast<QTile*>(plan + h.off_work)[rank] = mine;
+  }
 }
 
 // Longest-first order (stable): rank = number of tiles that must run before this one.
@@ -171,19 +210,31 @@ __global__ __launch_bounds__(256) void k_dense_mask(const int32_t* plan, PlanHea
     row[j] = (j < ae) || (j >= bs && j <= i) ? 1 : 0;
 }
 
-hipError_t launch_plan_kernels(int32_t* plan_dev, const PlanHeader& h, uint8_t* dense_mask,
-                               hipStream_t s) {
+hipError_t launch_plan_kernels(int32_t* plan_dev, const PlanHeader& h, const int32_t* host_ints,
+                               int n_img, uint8_t* dense_mask, hipStream_t s) {
+  hipError_t e;
   const int n1 = h.total_tokens > h.total_segments ? h.total_tokens : h.total_segments;
-  k_plan_tokens<<<dim3((n1 + 255) / 256), dim3(256), 0, s>>>(plan_dev, h);
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return e;
-  const int nt = (h.n_q_tiles + 255) / 256;
-  k_plan_tiles<<<dim3(nt), dim3(256), 0, s>>>(plan_dev, h);
-  e = hipGetLastError();
-  if (e != hipSuccess) return e;
-  k_plan_sort<<<dim3(nt), dim3(256), 0, s>>>(plan_dev, h);
-  e = hipGetLastError();
-  if (e != hipSuccess) return e;
+  if (n_img <= kUploadInts && n1 <= kSmallTokens && h.n_q_tiles <= kSmallTiles) {
+    UploadChunk c;
+    for (int i = 0; i < n_img; ++i) c.v[i] = host_ints[i];
+    for (int i = n_img; i < kUploadInts; ++i) c.v[i] = 0;
+    k_plan_small<<<dim3(1), dim3(1024), 0, s>>>(plan_dev, h, c, n_img);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  } else {
+    e = launch_upload(plan_dev, host_ints, n_img, s);
+    if (e != hipSuccess) return e;
+    k_plan_tokens<<<dim3((n1 + 255) / 256), dim3(256), 0, s>>>(plan_dev, h);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const int nt = (h.n_q_tiles + 255) / 256;
+    k_plan_tiles<<<dim3(nt), dim3(256), 0, s>>>(plan_dev, h);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    k_plan_sort<<<dim3(nt), dim3(256), 0, s>>>(plan_dev, h);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
   if (dense_mask) {
     k_dense_mask<<<dim3(h.total_tokens), dim3(256), 0, s>>>(plan_dev, h, dense_mask);
     e = hipGetLastError();
