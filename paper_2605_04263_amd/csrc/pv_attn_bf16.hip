@@ -258,6 +258,9 @@ __global__ __launch_bounds__(G * 64, 2) __attribute__((amdgpu_waves_per_eu(2))) 
   const int n_tiles = tile.n_a + (tile.jb1 - tile.jb0);
   const int n_steps = 2 * n_tiles;
   const int last = n_steps - 1;
+  // the plan lists the longest items first: they bound the run time, so their waves go first
+  // wherever they share a SIMD with a shorter item
+  if (blockIdx.x < gridDim.x / 4) __builtin_amdgcn_s_setprio(3);
   const int64_t head_base = ((int64_t)kvh * h.padded_keys + tile.kpad_base) * D;   // elements
   auto step_key0 = [&](int j) {           // first key (request-local) of step j
     const int idx = j >> 1;
@@ -538,49 +541,30 @@ __global__ __launch_bounds__(G * 64, 2) __attribute__((amdgpu_waves_per_eu(2))) 
   //   p_in  probabilities of step j (input)     p_out  probabilities of step j+1 (result)
   int slot_v = min(1, last) % NS, slot_k = min(3, last) % NS;   // slots of step j+1 and step j+3
   //   steady: both refills of this step exist and the pipeline is full, so the wait is a constant
-  //           and the refills are issued from inside the MFMA block (no branch splits the block)
+  //           and the staging loads are issued from inside the MFMA block (no branch splits it)
   int sj = 0;                                           // j % NS
   auto step = [&](int j, f32x16& s_in, f32x16& s_out, unsigned (&p_in)[8], unsigned (&p_out)[8],
                   auto last_of_pair, auto steady) {
     constexpr bool STEADY = decltype(steady)::value;
-    // All operand reads of the previous step have landed: its V^T slot (step j) and K slot (step
-    // j+2) can be refilled once every wave is here.  Steps up to j+3 (K) and j+1 (V^T) must be
-    // visible; everything issued after them may stay in flight:
-    //   K(j+4) .. K(j+1+NS) and V^T(j+2) .. V^T(j+NS-1), as far as they exist and were issued.
-    wait_kv();
-    if constexpr (STEADY && (2 * NS - 4) * HPW <= 63) {
-      __builtin_amdgcn_s_waitcnt(vmcnt_imm((2 * NS - 4) * HPW));
-    } else {
-      const int cnt_k = min(NS - 2, j + 2), cnt_v = min(NS - 2, j);
-      const int none_k = min(max(j + 1 + NS - last, 0), cnt_k);
-      const int none_v = min(max(j + NS - 1 - last, 0), cnt_v);
-      wait_slots(std::integral_constant<int, 2 * NS - 4>{}, cnt_k - none_k + cnt_v - none_v);
-    }
-    __builtin_amdgcn_s_barrier();
-    const int slot_ks = sj + 2 >= NS ? sj + 2 - NS : sj + 2;   // (j + 2) % NS
-    if constexpr (!STEADY) {
-      if (j + 2 + NS <= last) stage_k_to(j + 2 + NS, slot_ks);
-      if (j + NS <= last) stage_v_to(j + NS, sj);
-    }
     const bool have1 = !decltype(last_of_pair)::value || j + 1 <= last;
     if (have1) {
       const int key0 = step_key0(j + 1);
       if (key0 >= tile.n_full * 64) apply_mask(s_in, key0);
     }
-    __builtin_amdgcn_sched_barrier(0);
-
+    const int slot_ks = sj + 2 >= NS ? sj + 2 - NS : sj + 2;   // (j + 2) % NS
     const bf16x8 pfa = as_bf16x8(make_uint4(p_in[0], p_in[1], p_in[2], p_in[3]));
     const bf16x8 pfb = as_bf16x8(make_uint4(p_in[4], p_in[5], p_in[6], p_in[7]));
     float rs = 0.0f;
     const unsigned sbv = (unsigned)slot_v * SLOT_BYTES, sbk = (unsigned)slot_k * SLOT_BYTES;
-    // The block is 2 KT groups of one MFMA, one operand refill and a share of the VALU work, and
-    // the issue order is fixed group by group.  (Left to itself the scheduler clusters the MFMAs,
-    // and the VALU work then runs while the matrix pipe idles.)  The wave issues in order, so a
-    // VALU instruction waiting for its input also holds back the next MFMA: the softmax work of
-    // score i is therefore spread over consecutive groups,
+    // The step is 2 KT groups of one MFMA, at most one operand refill and a share of the VALU
+    // work, and the issue order is fixed group by group.  (Left to itself the scheduler clusters
+    // the MFMAs, and the VALU work then runs while the matrix pipe idles.)  The wave issues in
+    // order, so a VALU instruction waiting for its input also holds back the next MFMA: the
+    // softmax work of a score is therefore spread over consecutive groups,
     //   exponent argument -> exp2 -> (pair) bf16 pack -> (pair) row-sum dot,
     // each stage one group after the stage it depends on.
-    constexpr int NG = 2 * KT, SPG = 16 / NG;          // groups, scores per group
+    constexpr int NG = 2 * KT, SPG = 16 / NG;          // groups; scores entering per group
+    constexpr int HB = KT / 4;                         // k-steps issued before the barrier
     float ea[16], ex[16];                              // exponent arguments, exponentials
     auto v_arg = [&](auto i) {
       constexpr int I = decltype(i)::value;
@@ -606,25 +590,116 @@ __global__ __launch_bounds__(G * 64, 2) __attribute__((amdgpu_waves_per_eu(2))) 
                                                __builtin_bit_cast(bf16x2, 0x3f803f80u), rs, false);
       });
     };
-    static_for<0, SPG>([&](auto k) { v_arg(k); });
-    valu_group(std::integral_constant<int, -1>{});
-    __builtin_amdgcn_sched_barrier(0);
-    static_for<0, KT>([&](auto t) {
+    // n-th staging instruction of this wave for a slot
+    auto stage_one = [&](const char* src, unsigned lds0, auto n) {
+      constexpr int N = decltype(n)::value;
+      const int c = wave_s + N * G;
+      if ((CH32 / 64) % G == 0 || c < CH32 / 64) {
+        unsigned lo = lane16;
+        asm volatile("" : "+v"(lo));
+        __builtin_amdgcn_global_load_lds(
+            (const __attribute__((address_space(1))) void*)(src + c * 1024 + lo),
+            (__attribute__((address_space(3))) void*)(uintptr_t)(lds0 + c * 1024), 16, 0, 0);
+      }
+    };
+    const char* src_k = nullptr;
+    const char* src_v = nullptr;
+    if constexpr (STEADY) {
+      src_k = krot_b + (int64_t)step_key0(j + 2 + NS) * (D * 2);
+      src_v = vt_b + (int64_t)step_key0(j + NS) * (D * 2);
+    }
+    const unsigned lds_ks = smem_base + (unsigned)slot_ks * SLOT_BYTES;
+    const unsigned lds_vs = vring + (unsigned)sj * SLOT_BYTES;
+    // The 2 NREP staging instructions of this step (K slot first, then V^T slot) are dealt out
+    // over the body groups, one per group as long as there are enough groups.
+    constexpr int BG = 2 * (KT - HB);                  // body groups
+    auto stage_part2 = [&](auto bg) {
+      static_for<0, (2 * NREP + BG - 1) / BG>([&](auto m) {
+        constexpr int X = decltype(bg)::value + decltype(m)::value * BG;
+        if constexpr (X < NREP) stage_one(src_k, lds_ks, std::integral_constant<int, X>{});
+        else if constexpr (X < 2 * NREP) stage_one(src_v, lds_vs, std::integral_constant<int, X - NREP>{});
+      });
+    };
+    auto mfma_pv = [&](auto t) {
       constexpr int T = decltype(t)::value;
       constexpr int uu = T / DB, db = T % DB;
       o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[uu][db], uu ? pfb : pfa, o[db], 0, 0, 0);
-      lds_refill_b128<(uu * 2 * D + db * 32) * 16>(vf[uu][db], v_off + sbv);
-      valu_group(std::integral_constant<int, 2 * T>{});
-      __builtin_amdgcn_sched_barrier(0);
+    };
+    auto mfma_qk = [&](auto t) {
+      constexpr int T = decltype(t)::value;
       if constexpr (T == 0) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) s_out[r] = 0.0f;   // becomes the constant-zero accumulator input
       }
       s_out = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[t], qf[t], s_out, 0, 0, 0);
+    };
+    auto wait_operand = [&](bf16x8& r, auto n) {
+      constexpr int N = decltype(n)::value;
+      asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(r) : "n"(N));
+    };
+    auto refill_v = [&](auto t) {
+      constexpr int T = decltype(t)::value;
+      constexpr int uu = T / DB, db = T % DB;
+      lds_refill_b128<(uu * 2 * D + db * 32) * 16>(vf[uu][db], v_off + sbv);
+    };
+    auto refill_k = [&](auto t) {
+      constexpr int T = decltype(t)::value;
       lds_refill_b128<T * 1024>(kf[t], k_off + sbk);
+    };
+
+    static_for<0, SPG>([&](auto k) { v_arg(k); });
+    valu_group(std::integral_constant<int, -1>{});
+    __builtin_amdgcn_sched_barrier(0);
+    // Head: the first MFMAs need nothing from LDS, so they are issued before the barrier and run
+    // while this wave waits for the staging loads and for the other waves.
+    static_for<0, HB>([&](auto t) {
+      constexpr int T = decltype(t)::value;
+      // LDS reads land in order: the operand read as number x of the previous step's 16 is there
+      // once at most 15 - x younger reads are outstanding
+      wait_operand(vf[T / DB][T % DB], std::integral_constant<int, 2 * KT - 1 - 2 * T>{});
+      mfma_pv(t);
+      valu_group(std::integral_constant<int, 2 * T>{});
+      __builtin_amdgcn_sched_barrier(0);
+      wait_operand(kf[T], std::integral_constant<int, 2 * KT - 2 - 2 * T>{});
+      mfma_qk(t);
       valu_group(std::integral_constant<int, 2 * T + 1>{});
-      if constexpr (STEADY && T == 1) stage_k_to(j + 2 + NS, slot_ks);
-      if constexpr (STEADY && T == 2) stage_v_to(j + NS, sj);
+      __builtin_amdgcn_sched_barrier(0);
+    });
+    wait_kv();                                         // all reads of the previous step are done
+    // Every wave is past the operand reads of the previous step: its V^T slot (step j) and K slot
+    // (step j+2) can be refilled.  Steps up to j+3 (K) and j+1 (V^T) must be visible; everything
+    // issued after them may stay in flight:
+    //   K(j+4) .. K(j+1+NS) and V^T(j+2) .. V^T(j+NS-1), as far as they exist and were issued.
+    if constexpr (STEADY && (2 * NS - 4) * HPW <= 63) {
+      __builtin_amdgcn_s_waitcnt(vmcnt_imm((2 * NS - 4) * HPW));
+    } else {
+      const int cnt_k = min(NS - 2, j + 2), cnt_v = min(NS - 2, j);
+      const int none_k = min(max(j + 1 + NS - last, 0), cnt_k);
+      const int none_v = min(max(j + NS - 1 - last, 0), cnt_v);
+      wait_slots(std::integral_constant<int, 2 * NS - 4>{}, cnt_k - none_k + cnt_v - none_v);
+    }
+    __builtin_amdgcn_s_barrier();
+    if constexpr (!STEADY) {
+      if (j + 2 + NS <= last) stage_k_to(j + 2 + NS, slot_ks);
+      if (j + NS <= last) stage_v_to(j + NS, sj);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    static_for<0, HB>([&](auto t) { refill_v(t); refill_k(t); });
+    __builtin_amdgcn_sched_barrier(0);
+    // Body: every MFMA is followed by the refill of its operand; in steady state the staging
+    // instructions of this step are spread over the groups, K first.
+    static_for<HB, KT>([&](auto t) {
+      constexpr int T = decltype(t)::value;
+      constexpr int R = T - HB;                        // 0, 1, ...
+      mfma_pv(t);
+      refill_v(t);
+      valu_group(std::integral_constant<int, 2 * T>{});
+      if constexpr (STEADY) stage_part2(std::integral_constant<int, 2 * R>{});
+      __builtin_amdgcn_sched_barrier(0);
+      mfma_qk(t);
+      refill_k(t);
+      valu_group(std::integral_constant<int, 2 * T + 1>{});
+      if constexpr (STEADY) stage_part2(std::integral_constant<int, 2 * R + 1>{});
       __builtin_amdgcn_sched_barrier(0);
     });
     valu_group(std::integral_constant<int, NG>{});     // what is left: the last row-sum term
@@ -664,12 +739,10 @@ __global__ __launch_bounds__(G * 64, 2) __attribute__((amdgpu_waves_per_eu(2))) 
     const float inv = 1.0f / l_tot;
     const int64_t tok0 = (int64_t)tile.tok_base + tile.t0;
     // rows with few visible keys are produced in fp32 by the preparation kernel: not stored here
-    auto stored = [&](int row) {
-      if (row >= tile.rows) return false;
-      const int64_t gg = tok0 + row;
-      const int cnt = plan[h.off_aend + gg] + (tile.t0 + row) - plan[h.off_bstart + gg] + 1;
-      return cnt > PV_SHORT_ROW_KEYS;
-    };
+    // (lane r < 32 holds the descriptor of row r: one ballot gives the row mask to every lane)
+    const unsigned stored_rows = (unsigned)__builtin_amdgcn_ballot_w64(
+        valid && a_end + i_loc - b_start + 1 > PV_SHORT_ROW_KEYS);
+    auto stored = [&](int row) { return ((stored_rows >> row) & 1u) != 0; };
     constexpr int RS = 2 * D + 16;                    // row stride: 16 B of padding spreads the banks
     char* tr = reinterpret_cast<char*>(&smem[0]) + (size_t)wave * (32 * RS);
     if (out_f32) {
