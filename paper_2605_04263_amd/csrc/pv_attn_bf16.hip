@@ -103,9 +103,9 @@ __device__ void short_row(const int32_t* __restrict__ plan, const PlanHeader& h,
   }
 }
 
-// grid = padded_keys / 16 blocks of 16 keys (all kv heads each), then one block per (short row,
-// kv head).  Pad rows (beyond the request) are written as 0 so that masked probabilities (exactly
-// 0) never meet a non-finite value.
+// grid = one block per (short row, kv head) first (they take longest, so they start first), then
+// blocks of 16 keys x 2 kv heads.  Pad rows (beyond the request) are written as 0 so that masked
+// probabilities (exactly 0) never meet a non-finite value.
 template <int D>
 __global__ __launch_bounds__(256) void k_prep_kv(const int32_t* __restrict__ plan, PlanHeader h,
                                                  const uint16_t* __restrict__ k,
@@ -115,10 +115,10 @@ __global__ __launch_bounds__(256) void k_prep_kv(const int32_t* __restrict__ pla
                                                  uint16_t* __restrict__ vt, ShortRowArgs sr) {
   constexpr int HALF = D / 2;
   constexpr int KB = 16;                       // keys per block
-  constexpr int HG = 8;                        // kv heads handled per pass
-  const int n_main = h.padded_keys / KB;
-  if ((int)blockIdx.x >= n_main) {             // extra blocks: one (short row, kv head) each
-    const int idx = (int)blockIdx.x - n_main;
+  constexpr int HG = 2;                        // kv heads per block
+  const int n_short_blocks = h.n_short_rows * hkv;
+  if ((int)blockIdx.x < n_short_blocks) {      // one (short row, kv head) each
+    const int idx = (int)blockIdx.x;
     const int g = plan[h.off_short + idx / hkv], kvh = idx % hkv;
     const int G = sr.hq / hkv;
     for (int hl = threadIdx.x >> 6; hl < G; hl += 4)
@@ -127,7 +127,11 @@ __global__ __launch_bounds__(256) void k_prep_kv(const int32_t* __restrict__ pla
   }
   __shared__ float2 cs_s[KB][HALF];            // cos/sin of the block's tokens
   __shared__ uint4 v_s[HG][KB][D / 8 + 1];     // V rows of one pass, padded
-  const int row0 = blockIdx.x * KB;            // first padded key row of this block
+  const int n_hg = (hkv + HG - 1) / HG;        // head groups
+  const int mb = (int)blockIdx.x - n_short_blocks;
+  const int row0 = (mb / n_hg) * KB;           // first padded key row of this block
+  const int h0 = (mb % n_hg) * HG;             // first kv head of this block
+  const int nh = min(HG, hkv - h0);
   // owner request of the block (requests are padded to multiples of 64 keys)
   const int32_t* kp = plan + h.off_kpad_start;
   int lo = 0, hi = h.batch;
@@ -152,14 +156,13 @@ __global__ __launch_bounds__(256) void k_prep_kv(const int32_t* __restrict__ pla
         double sn, cn;
         sincos((double)plan[h.off_pos + g] * f.inv_freq[c], &sn, &cn);
         t = make_float2((float)cn, (float)sn);
-        cs[g * HALF + c] = t;
+        if (h0 == 0) cs[g * HALF + c] = t;
       }
       cs_s[key][c] = t;
     }
   }
-  for (int h0 = 0; h0 < hkv; h0 += HG) {
-    const int nh = min(HG, hkv - h0);
-    __syncthreads();                           // cs_s ready; v_s free
+  {
+    __syncthreads();                           // cs_s ready
     // V rows into LDS with 16-byte loads
     for (int item = tid; item < nh * KB * (D / 8); item += 256) {
       const int ch = item % (D / 8), hl = (item / (D / 8)) % nh, key = item / ((D / 8) * nh);
@@ -832,7 +835,7 @@ hipError_t launch_attn_bf16(const int32_t* plan_dev, const PlanHeader& h, const 
   const uint16_t* kv = reinterpret_cast<const uint16_t*>(v);
   hipError_t e;
   {
-    const dim3 grid((unsigned)(h.padded_keys / 16 + h.n_short_rows * hkv));
+    const dim3 grid((unsigned)((h.padded_keys / 16) * ((hkv + 1) / 2) + h.n_short_rows * hkv));
     ShortRowArgs sr;
     sr.q = kq; sr.out = out; sr.lse = lse; sr.hq = hq; sr.scale = scale; sr.out_f32 = out_dtype == PV_F32;
     if (d == 64) k_prep_kv<64><<<grid, dim3(256), 0, s>>>(plan_dev, h, kk, kv, freq, cs, hkv, rope, krot, vt, sr);
