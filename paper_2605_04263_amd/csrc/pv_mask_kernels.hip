@@ -171,29 +171,22 @@ __global__ __launch_bounds__(1024) void k_plan_small(int32_t* plan, PlanHeader h
   }
 }
 
-// Longest-first order (stable): rank = number of tiles that must run before this one.
+// Longest-first order (stable): rank = number of tiles that must run before this one.  One wave
+// per tile; its lanes share the comparisons against all other tiles.
 __global__ __launch_bounds__(256) void k_plan_sort(int32_t* plan, PlanHeader h) {
-  const int t = blockIdx.x * blockDim.x + threadIdx.x;
+  const int t = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+  if (t >= h.n_q_tiles) return;                 // whole waves leave together
   const QTile* tiles = reinterpret_cast<const QTile*>(plan + h.off_tiles);
-  __shared__ int cost_s[256];
-  QTile mine;
-  int my_cost = 0, rank = 0;
-  if (t < h.n_q_tiles) {
-    mine = tiles[t];
-    my_cost = mine.n_a + (mine.jb1 - mine.jb0);
+  const QTile mine = tiles[t];
+  const int my_cost = mine.n_a + (mine.jb1 - mine.jb0);
+  int rank = 0;
+  for (int u = lane; u < h.n_q_tiles; u += 64) {
+    const int c = tiles[u].n_a + (tiles[u].jb1 - tiles[u].jb0);
+    rank += (c > my_cost) || (c == my_cost && u < t);
   }
-  for (int base = 0; base < h.n_q_tiles; base += 256) {
-    const int u = base + threadIdx.x;
-    __syncthreads();
-    cost_s[threadIdx.x] = (u < h.n_q_tiles) ? tiles[u].n_a + (tiles[u].jb1 - tiles[u].jb0) : -1;
-    __syncthreads();
-    const int m = min(256, h.n_q_tiles - base);
-    for (int x = 0; x < m; ++x) {
-      const int c = cost_s[x];
-      rank += (c > my_cost) || (c == my_cost && base + x < t);
-    }
-  }
-  if (t < h.n_q_tiles) reinterpret_cast<QTile*>(plan + h.off_work)[rank] = mine;
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) rank += __shfl_xor(rank, off);
+  if (lane == 0) reinterpret_cast<QTile*>(plan + h.off_work)[rank] = mine;
 }
 
 // Dense mask from the stored row descriptors (what the attention kernels consume).
@@ -231,7 +224,7 @@ hipError_t launch_plan_kernels(int32_t* plan_dev, const PlanHeader& h, const int
     k_plan_tiles<<<dim3(nt), dim3(256), 0, s>>>(plan_dev, h);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
-    k_plan_sort<<<dim3(nt), dim3(256), 0, s>>>(plan_dev, h);
+    k_plan_sort<<<dim3((h.n_q_tiles + 3) / 4), dim3(256), 0, s>>>(plan_dev, h);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
   }
