@@ -97,6 +97,18 @@ def test_edge_cases(idx):
     check_full(w)
 
 
+# Every GQA group size the library accepts, both head sizes, on a request long enough for the
+# steady-state part of the key loop (all ring slots in flight) and with a masked tail: 33 tiles of
+# 32 rows, up to 17 key tiles per row tile.
+@pytest.mark.parametrize("d", [64, 128])
+@pytest.mark.parametrize("group", [1, 2, 3, 4, 5, 6, 7, 8])
+def test_group_sizes_long_rows(group, d):
+    pr = wl.Problem([70], [850], [3], [40], [[333, 600, 850]])
+    theta = 5e5 if group % 2 else 0.0
+    w = wl.make_custom(pr, group, 1, d, dtype=torch.bfloat16, rope_theta=theta, seed=300 + 8 * (d // 64) + group)
+    check_full(w)
+
+
 def test_tiny_shape_in_bf16():
     t = wl.make("tiny", rope_theta=5e5)
     w = wl.make_custom(t.problem, 1, 1, 64, dtype=torch.bfloat16, rope_theta=5e5, seed=7)

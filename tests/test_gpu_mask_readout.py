@@ -112,3 +112,77 @@ def test_readout_ties_and_k0():
     exp = orc.first_reject(lg, pr.num_segments, pr.boundaries, 0.0, 0)
     assert np.array_equal(got, exp)
     assert got[1].tolist() == [0, -1, 0, 0]
+
+
+def _work_list(ver):
+    """The tile work list as the attention kernel reads it, parsed from the plan blob (header of 32
+    ints: n_q_tiles at 4, tile_m at 5, tile_n at 6, off_tiles at 24, off_work at 25)."""
+    blob = ver.plan.view(torch.int32).cpu().numpy()
+    n, off_tiles, off_work = int(blob[4]), int(blob[24]), int(blob[25])
+    assert blob[5] == 32 and blob[6] == 64
+    tiles = blob[off_tiles:off_tiles + 8 * n].reshape(n, 8)
+    work = blob[off_work:off_work + 8 * n].reshape(n, 8)
+    return tiles, work
+
+
+def check_work_list(pr):
+    """Tile classifier against the oracle's dense mask: every visible (row, key) pair lies in a listed
+    key tile, tiles listed as fully visible are, and the work list is the tile list sorted longest
+    first (stable)."""
+    w = wl.make_custom(pr, 4, 2, 64, dtype=torch.float32, seed=1)
+    ver = gc.make_verifier(pv, w)
+    ver.build_mask()
+    torch.cuda.synchronize()
+    tiles, work = _work_list(ver)
+    cu = pr.token_offsets()
+    t = 0
+    for b in range(pr.batch):
+        n = pr.seq_len(b)
+        M = orc.dense_mask(pr.prompt_len[b], pr.draft_len[b], pr.segment_len[b], pr.boundaries[b])
+        nkt = (n + 63) // 64
+        Mp = np.zeros((n, nkt * 64), dtype=np.uint8)
+        Mp[:, :n] = M
+        for t0 in range(0, n, 32):
+            tok_base, tt0, rows, n_full, n_a, jb0, jb1, _ = (int(x) for x in tiles[t])
+            assert (tok_base, tt0, rows) == (cu[b], t0, min(32, n - t0))
+            blk = Mp[t0:t0 + rows].reshape(rows, nkt, 64)
+            any_vis = blk.any(axis=(0, 2))
+            all_vis = blk.all(axis=(0, 2))
+            listed = np.zeros(nkt, dtype=bool)
+            listed[:n_a] = True
+            listed[jb0:jb1] = True
+            assert 0 <= n_full <= n_a <= jb0 <= jb1 <= nkt
+            assert not (any_vis & ~listed).any(), (b, t0)            # nothing visible is skipped
+            assert all_vis[:n_full].all(), (b, t0)                   # unmasked tiles really are
+            # the classifier is tight: listed tiles hold a visible pair, except inside the gap-free
+            # ranges it is allowed to over-cover (none for these layouts)
+            assert any_vis[listed].all(), (b, t0)
+            t += 1
+    assert t == len(tiles)
+    cost = tiles[:, 4] + (tiles[:, 6] - tiles[:, 5])
+    order = np.argsort(-cost, kind="stable")
+    assert np.array_equal(work, tiles[order])
+
+
+@pytest.mark.parametrize("idx", range(len(EDGE_PROBLEMS)))
+def test_work_list_edge_cases(idx):
+    check_work_list(EDGE_PROBLEMS[idx])
+
+
+def test_work_list_8b_single_launch_plan():
+    check_work_list(wl.make("8b").problem)
+
+
+def test_work_list_multi_kernel_plan():
+    # more than 8192 tokens: the plan is built by the separate upload / tokens / tiles / ranking
+    # kernels instead of the single-workgroup kernel
+    rng = np.random.default_rng(11)
+    B = 6
+    P = [int(x) for x in rng.integers(0, 700, B)]
+    T = [int(x) for x in rng.integers(3000, 6000, B)]
+    K = [int(x) for x in rng.integers(0, 9, B)]
+    S = [int(x) for x in rng.integers(1, 70, B)]
+    bounds = [sorted(int(x) for x in rng.integers(0, T[b] + 1, K[b])) for b in range(B)]
+    pr = wl.Problem(P, T, K, S, bounds)
+    assert pr.total_tokens > 8192
+    check_work_list(pr)
