@@ -169,6 +169,17 @@ def main() -> int:
     pv.pv_profile_enable(False)
     kernel_ms = sum(ks) / len(ks)
 
+    # the decision calls that follow the readout (not part of the timed step): lm-head gather of
+    # the judge logits from hidden states of a 4096-wide model, and the full decision policy
+    hid = torch.randn(pr.total_tokens, 4096, device=dev).bfloat16()
+    w2 = (torch.randn(2, 4096, device=dev) * 0.05).bfloat16()
+    full_lg = torch.zeros(pr.batch, 2, device=dev)
+    pol = pv.make_policy(thr, pv.margin_from_tau(0.90), pv.margin_from_tau(0.998), pv.margin_from_tau(0.95),
+                         [pv.margin_from_tau(0.95)] * 2, 0.30, 2, 0.0)
+    t_judge = timed(lambda: ver.judge_logits(hid, w2), n_b)
+    t_decide = timed(lambda: ver.decide(logits, full_lg, pol), n_b)
+    del hid
+
     achieved = eff_flops / (kernel_ms * 1e-3) / 1e12
     traffic = MEASURED_TRAFFIC_BYTES.get(w.name)
     line = {
@@ -186,6 +197,7 @@ def main() -> int:
         "verified_prefixes_per_s": pr.total_segments / (ms_per_step * 1e-3),
         "breakdown_ms": {"pv_build_mask": t_build, "pv_masked_attention": t_attn, "pv_first_reject": t_read,
                          "attention_main_kernel": kernel_ms},
+        "after_step_ms": {"pv_judge_logits_h4096": t_judge, "pv_decide": t_decide},
         "attn_tflops": eff_flops / (t_attn * 1e-3) / 1e12,
         "roofline": {"bound": "mfma", "kernel": "k_attn_bf16", "achieved": achieved,
                      "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",

@@ -132,6 +132,60 @@ pv_status pv_masked_attention(const pv_sizes* sizes, const void* plan_dev, const
 pv_status pv_first_reject(const pv_sizes* sizes, const void* plan_dev, const float* logits_dev,
                           double margin_threshold, int32_t mode, int32_t* out_dev, void* stream);
 
+/* Judge logits.  For every segment k of every request, the hidden state at its judge row (the
+ * last token of the segment, where the verifier's answer is read) times the two lm-head rows of
+ * the Correct and Incorrect tokens (appendix "Notation and judge calibration": the verifier's
+ * logits l_C, l_I at the judgment position).  bf16 inputs, fp32 accumulation.
+ *   hidden_dev   device bf16 [total_tokens][hidden_size], 16-byte aligned, not modified
+ *   w2_dev       device bf16 [2][hidden_size]: row 0 = Correct token, row 1 = Incorrect token
+ *   hidden_size  multiple of 8, 8 .. 65536
+ *   logits_dev   device float [total_segments][2] = (l_C, l_I): the input of pv_first_reject /
+ *                pv_decide */
+pv_status pv_judge_logits(const pv_sizes* sizes, const void* plan_dev, const void* hidden_dev,
+                          const void* w2_dev, int32_t hidden_size, float* logits_dev,
+                          void* stream);
+
+/* Decision policy of the detailed algorithm (appendix "Full pipeline") once the judge logits are
+ * known.  Every confidence threshold tau is given as the logit margin ln(tau / (1 - tau)), and a
+ * confidence p_2w >= tau is tested as l_C - l_I >= margin in fp64 (see pv_first_reject). */
+#define PV_MAX_SHORT_CHUNKS 8
+typedef struct {
+  double margin_chunk;          /* strict per-chunk threshold tau_P */
+  double margin_chunk_relaxed;  /* relaxed per-chunk threshold tau_C^rx */
+  double margin_full;           /* strict full-verify threshold tau_F */
+  double margin_full_relaxed;   /* relaxed full-verify threshold tau_F^rx */
+  double margin_short[PV_MAX_SHORT_CHUNKS]; /* short-draft threshold for K = 1 .. n_short chunks:
+                                   min(tau_sd + 0.02 (K - 1), tau_F^rx) */
+  double rho;                   /* the chunk run rejects when n_incorrect / K exceeds rho ... */
+  double eta;                   /* rollback margin in chunks, >= 0 */
+  int32_t kappa;                /* ... or the trailing run of Incorrect chunks reaches kappa (0: off) */
+  int32_t n_short;              /* short-draft ceiling K^sd, 0 .. PV_MAX_SHORT_CHUNKS */
+  int32_t relaxed_count_min;    /* premature exit: this many chunks below tau_C^rx abort (paper: 3) */
+  int32_t premature;            /* 0: Stages 2-6;  1: premature-PV early exit (pass rho_p as rho) */
+} pv_policy;
+
+enum { PV_LABEL_SM = 0, PV_LABEL_SM_LG = 1, PV_LABEL_LG = 2 };
+
+/* Per request writes 12 int32:
+ *   [0] label         PV_LABEL_SM ship the draft, PV_LABEL_SM_LG continue from L*, PV_LABEL_LG
+ *                     restart; premature mode without abort: -1 (keep drafting)
+ *   [1] stage         stage that decided (2 strict accept, 3 short-draft accept, 5 relaxed accept,
+ *                     6 hand-off); premature mode: 1 abort, 0 go on
+ *   [2] L*            adopted prefix: boundary p_{m-1}, m = floor(max(0, k* + 1 - eta)); 0 if m = 0
+ *   [3] k*            largest Correct chunk with no Incorrect before it, -1 if none
+ *   [4] first_reject  [5] n_incorrect  [6] trailing run of Incorrect chunks
+ *   [7] 1 if the rho / kappa rules reject the chunk run
+ *   [8] chunks whose confidence is below tau_C^rx
+ *   [9] full-answer verdict at tau_F (premature mode: -1)
+ *   [10] index of the least confident chunk (first of equals; -1 if K = 0)   [11] K
+ *   logits_dev       device float [total_segments][2]
+ *   full_logits_dev  device float [B][2] (l_C^F, l_I^F) of the full-answer judge; NULL allowed in
+ *                    premature mode only
+ *   out_dev          device int32 [B][12], 16-byte aligned */
+pv_status pv_decide(const pv_sizes* sizes, const void* plan_dev, const float* logits_dev,
+                    const float* full_logits_dev, const pv_policy* policy, int32_t* out_dev,
+                    void* stream);
+
 /* Copies of the plan's per-token / per-segment arrays for inspection (device to device, on
  * `stream`): positions, a_end, b_start are int32 [total_tokens]; judge_row is int32
  * [total_segments] (row index into the packed token dimension).  Any output may be NULL. */

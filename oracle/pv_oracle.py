@@ -222,3 +222,106 @@ def first_reject(logits: np.ndarray, num_segments: Sequence[int], boundaries, th
         out[b] = (first, k_star, L_star, int(K - ok.sum()))
         start += K
     return out
+
+
+# --------------------------------------------------------------------------- decision policy
+
+LABEL_SM, LABEL_SM_LG, LABEL_LG = 0, 1, 2          # ship the draft / continue from L* / restart
+
+
+def chunk_run_rules(ok: np.ndarray, rho: float, kappa: int):
+    """The two reject rules of "Parallel partial verify" on a verdict sequence: the run of chunks
+    rejects the draft when the fraction of Incorrect chunks exceeds rho, or when the trailing run of
+    Incorrect chunks reaches kappa.  Returns (rejects, n_incorrect, trailing_incorrect)."""
+    K = len(ok)
+    n_inc = int(K - int(np.sum(ok)))
+    trailing = 0
+    for kk in range(K - 1, -1, -1):
+        if ok[kk]:
+            break
+        trailing += 1
+    frac_rule = K > 0 and float(n_inc) > float(rho) * float(K)
+    run_rule = kappa > 0 and trailing >= kappa
+    return bool(frac_rule or run_rule), n_inc, trailing
+
+
+def adopted_prefix(k_star: int, eta: float, bounds: Sequence[int]) -> int:
+    """Adopted-prefix length (the equation of that name): roll back eta chunks from the last correct
+    boundary.  With chunk k ending at draft token bounds[k], Delta * floor(max(0, k* + 1 - eta))
+    chunks kept means L* = bounds[m - 1] with m = floor(max(0, k* + 1 - eta)), and 0 for m = 0."""
+    m = int(math.floor(max(0.0, float(k_star) + 1.0 - float(eta))))
+    return int(bounds[m - 1]) if m >= 1 else 0
+
+
+def decide(logits: np.ndarray, full_logits, num_segments: Sequence[int], boundaries, *,
+           margin_chunk: float, margin_chunk_relaxed: float, margin_full: float,
+           margin_full_relaxed: float, margin_short: Sequence[float], rho: float, kappa: int,
+           eta: float, relaxed_count_min: int = 3, premature: bool = False) -> np.ndarray:
+    """Per request the decision of the detailed algorithm after the judge logits are known.
+
+    premature = False: Stages 2-6.  Stage 2 accepts when the full-answer verdict is Correct at
+      the strict threshold; Stage 3 accepts drafts of at most len(margin_short) chunks whose
+      full-answer confidence reaches the short-draft threshold of that chunk count
+      (margin_short[K-1], already combined with the relaxed full threshold by the caller);
+      Stage 5 accepts when the full-answer confidence reaches the relaxed threshold and every
+      chunk's confidence reaches the relaxed chunk threshold; Stage 6 continues from L* > 0 or
+      restarts.  All confidences are compared as fp64 logit margins.
+    premature = True: the premature-PV early exit: abort drafting when the chunk rules reject (with
+      the rho passed) or at least relaxed_count_min chunks are below the relaxed chunk threshold.
+
+    Returns int32 [B, 12]: label (premature without abort: -1), deciding stage (2, 3, 5, 6;
+    premature: 1 abort / 0 go on), L*,
+    k*, first_reject, n_incorrect, trailing_incorrect, chunk_rules_reject, n_below_relaxed,
+    full verdict (premature: -1), index of the least confident chunk (-1 if K = 0), K.
+    """
+    B = len(num_segments)
+    out = np.zeros((B, 12), dtype=np.int32)
+    start = 0
+    for b, K in enumerate(num_segments):
+        lg = logits[start:start + K]
+        d = lg[:, 0].astype(np.float64) - lg[:, 1].astype(np.float64)
+        ok = (d >= 0.0) & (d >= margin_chunk)
+        first = K
+        for kk in range(K):
+            if not ok[kk]:
+                first = kk
+                break
+        k_star = first - 1
+        rejects, n_inc, trailing = chunk_run_rules(ok, rho, kappa)
+        n_below = int(np.sum(d < margin_chunk_relaxed))
+        argmin = int(np.argmin(d)) if K > 0 else -1       # first index of the minimum
+        L_star = adopted_prefix(k_star, eta, boundaries[b])
+        if premature:
+            abort = rejects or n_below >= relaxed_count_min
+            label = (LABEL_SM_LG if L_star > 0 else LABEL_LG) if abort else -1   # -1: keep drafting
+            out[b] = (label, 1 if abort else 0, L_star, k_star, first, n_inc, trailing, int(rejects),
+                      n_below, -1, argmin, K)
+        else:
+            dF = float(np.float64(full_logits[b][0]) - np.float64(full_logits[b][1]))
+            vF = dF >= 0.0 and dF >= margin_full
+            if vF:
+                label, stage = LABEL_SM, 2
+            elif 1 <= K <= len(margin_short) and dF >= margin_short[K - 1]:
+                label, stage = LABEL_SM, 3
+            elif dF >= margin_full_relaxed and n_below == 0:
+                label, stage = LABEL_SM, 5
+            else:
+                label, stage = (LABEL_SM_LG if L_star > 0 else LABEL_LG), 6
+            out[b] = (label, stage, L_star, k_star, first, n_inc, trailing, int(rejects), n_below,
+                      int(vF), argmin, K)
+        start += K
+    return out
+
+
+def short_draft_margins(tau_sd: float, tau_full_relaxed: float, max_chunks: int):
+    """Short-draft thresholds of Stage 3 as margins: tau(K) = min(tau_sd + 0.02 (K - 1),
+    tau_full_relaxed) for K = 1 .. max_chunks."""
+    return [margin_threshold(min(tau_sd + 0.02 * (K - 1), tau_full_relaxed))
+            for K in range(1, max_chunks + 1)]
+
+
+def judge_logits(hidden: np.ndarray, w2: np.ndarray, rows: np.ndarray) -> np.ndarray:
+    """(l_C, l_I) of every judged position: the hidden state at that row times the two lm-head
+    rows of the Correct and Incorrect tokens, in fp64.  hidden [tokens, H], w2 [2, H]."""
+    h = hidden[np.asarray(rows, dtype=np.int64)].astype(np.float64)
+    return h @ w2.astype(np.float64).T

@@ -42,6 +42,19 @@ class PvSizes(C.Structure):
                 ("n_short_rows", C.c_int32), ("reserved", C.c_int32)]
 
 
+PV_MAX_SHORT_CHUNKS = 8
+PV_LABEL_SM, PV_LABEL_SM_LG, PV_LABEL_LG = 0, 1, 2
+
+
+class PvPolicy(C.Structure):
+    _fields_ = [("margin_chunk", C.c_double), ("margin_chunk_relaxed", C.c_double),
+                ("margin_full", C.c_double), ("margin_full_relaxed", C.c_double),
+                ("margin_short", C.c_double * PV_MAX_SHORT_CHUNKS),
+                ("rho", C.c_double), ("eta", C.c_double),
+                ("kappa", C.c_int32), ("n_short", C.c_int32),
+                ("relaxed_count_min", C.c_int32), ("premature", C.c_int32)]
+
+
 def _load() -> C.CDLL:
     if not os.path.exists(LIB_PATH):
         raise ImportError(f"{LIB_PATH} is not built: run `python -c 'import __graft_entry__ as g; g.build()'`")
@@ -57,10 +70,15 @@ def _load() -> C.CDLL:
                                     C.c_void_p, C.c_void_p]
     lib.pv_plan_export.argtypes = [P(PvSizes), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                    C.c_void_p, C.c_void_p]
+    lib.pv_judge_logits.argtypes = [P(PvSizes), C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32,
+                                    C.c_void_p, C.c_void_p]
+    lib.pv_decide.argtypes = [P(PvSizes), C.c_void_p, C.c_void_p, C.c_void_p, P(PvPolicy),
+                              C.c_void_p, C.c_void_p]
     lib.pv_profile_enable.argtypes = [C.c_int32]
     lib.pv_profile_read.argtypes = [P(C.c_float)]
     for name in ("pv_query_sizes", "pv_build_mask", "pv_masked_attention", "pv_first_reject",
-                 "pv_plan_export", "pv_profile_enable", "pv_profile_read", "pv_last_hip_error"):
+                 "pv_plan_export", "pv_profile_enable", "pv_profile_read", "pv_last_hip_error",
+                 "pv_judge_logits", "pv_decide"):
         getattr(lib, name).restype = C.c_int32
     lib.pv_strerror.argtypes = [C.c_int32]
     lib.pv_strerror.restype = C.c_char_p
@@ -167,6 +185,48 @@ def pv_first_reject(sizes: PvSizes, plan: torch.Tensor, logits: torch.Tensor, ma
                                margin_threshold, mode, _ptr(out), _stream()), "pv_first_reject")
 
 
+def pv_judge_logits(sizes: PvSizes, plan: torch.Tensor, hidden: torch.Tensor, w2: torch.Tensor,
+                    logits: torch.Tensor) -> None:
+    if hidden.dtype != torch.bfloat16 or hidden.dim() != 2 or hidden.shape[0] != sizes.total_tokens:
+        raise ValueError("hidden must be bfloat16 [total_tokens, hidden_size]")
+    if w2.dtype != torch.bfloat16 or tuple(w2.shape) != (2, hidden.shape[1]):
+        raise ValueError("w2 must be bfloat16 [2, hidden_size]")
+    if logits.dtype != torch.float32 or tuple(logits.shape) != (sizes.total_segments, 2):
+        raise ValueError("logits must be float32 [total_segments, 2]")
+    if not (hidden.is_contiguous() and w2.is_contiguous() and logits.is_contiguous()):
+        raise ValueError("tensors must be contiguous")
+    _check(lib.pv_judge_logits(C.byref(sizes), _ptr(plan), _ptr(hidden), _ptr(w2), hidden.shape[1],
+                               _ptr(logits) if logits.numel() else None, _stream()), "pv_judge_logits")
+
+
+def make_policy(margin_chunk: float, margin_chunk_relaxed: float, margin_full: float,
+                margin_full_relaxed: float, margin_short: Sequence[float], rho: float, kappa: int,
+                eta: float, relaxed_count_min: int = 3, premature: bool = False) -> PvPolicy:
+    if len(margin_short) > PV_MAX_SHORT_CHUNKS:
+        raise ValueError("too many short-draft thresholds")
+    pol = PvPolicy()
+    pol.margin_chunk, pol.margin_chunk_relaxed = margin_chunk, margin_chunk_relaxed
+    pol.margin_full, pol.margin_full_relaxed = margin_full, margin_full_relaxed
+    for i, m in enumerate(margin_short):
+        pol.margin_short[i] = m
+    pol.rho, pol.eta, pol.kappa, pol.n_short = rho, eta, kappa, len(margin_short)
+    pol.relaxed_count_min, pol.premature = relaxed_count_min, 1 if premature else 0
+    return pol
+
+
+def pv_decide(sizes: PvSizes, plan: torch.Tensor, logits: torch.Tensor,
+              full_logits: Optional[torch.Tensor], policy: PvPolicy, out: torch.Tensor) -> None:
+    if logits.dtype != torch.float32 or tuple(logits.shape) != (sizes.total_segments, 2):
+        raise ValueError("logits must be float32 [total_segments, 2]")
+    if full_logits is not None and (full_logits.dtype != torch.float32 or
+                                    tuple(full_logits.shape) != (sizes.batch, 2)):
+        raise ValueError("full_logits must be float32 [batch, 2]")
+    if out.dtype != torch.int32 or tuple(out.shape) != (sizes.batch, 12):
+        raise ValueError("out must be int32 [batch, 12]")
+    _check(lib.pv_decide(C.byref(sizes), _ptr(plan), _ptr(logits) if logits.numel() else None,
+                         _ptr(full_logits), C.byref(policy), _ptr(out), _stream()), "pv_decide")
+
+
 def pv_plan_export(sizes: PvSizes, plan: torch.Tensor):
     """(positions, a_end, b_start, judge_row) as int32 device tensors."""
     dev = plan.device
@@ -221,3 +281,13 @@ class Verifier:
     def first_reject(self, logits, margin_threshold: float, mode: int = 0):
         pv_first_reject(self.sizes, self.plan, logits, margin_threshold, mode, self.readout)
         return self.readout
+
+    def judge_logits(self, hidden, w2):
+        logits = torch.empty(self.sizes.total_segments, 2, dtype=torch.float32, device=self.device)
+        pv_judge_logits(self.sizes, self.plan, hidden, w2, logits)
+        return logits
+
+    def decide(self, logits, full_logits, policy: PvPolicy):
+        out = torch.empty(self.sizes.batch, 12, dtype=torch.int32, device=self.device)
+        pv_decide(self.sizes, self.plan, logits, full_logits, policy, out)
+        return out

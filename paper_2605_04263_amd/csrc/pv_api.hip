@@ -345,6 +345,56 @@ pv_status pv_first_reject(const pv_sizes* sizes, const void* plan_dev, const flo
   return PV_OK;
 }
 
+pv_status pv_judge_logits(const pv_sizes* sizes, const void* plan_dev, const void* hidden_dev,
+                          const void* w2_dev, int32_t hidden_size, float* logits_dev,
+                          void* stream) {
+  PlanHeader h;
+  pv_status st = check_sizes(sizes, &h);
+  if (st != PV_OK) return st;
+  if (!plan_dev) return PV_ERR_NULL;
+  if (hidden_size < 8 || hidden_size > 65536 || hidden_size % 8 != 0) return PV_ERR_SHAPE;
+  if (sizes->total_segments > 0 && (!hidden_dev || !w2_dev || !logits_dev)) return PV_ERR_NULL;
+  if (misaligned(plan_dev) || misaligned(hidden_dev) || misaligned(w2_dev) ||
+      ((uintptr_t)logits_dev & 7u))
+    return PV_ERR_ALIGN;
+  st = arch_ok_cached();
+  if (st != PV_OK) return st;
+  hipError_t e = launch_judge_logits((const int32_t*)plan_dev, h, hidden_dev, w2_dev, hidden_size,
+                                     logits_dev, (hipStream_t)stream);
+  if (e != hipSuccess) return hip_fail(e);
+  return PV_OK;
+}
+
+pv_status pv_decide(const pv_sizes* sizes, const void* plan_dev, const float* logits_dev,
+                    const float* full_logits_dev, const pv_policy* policy, int32_t* out_dev,
+                    void* stream) {
+  PlanHeader h;
+  pv_status st = check_sizes(sizes, &h);
+  if (st != PV_OK) return st;
+  if (!plan_dev || !out_dev || !policy) return PV_ERR_NULL;
+  if (sizes->total_segments > 0 && !logits_dev) return PV_ERR_NULL;
+  if (policy->premature != 0 && policy->premature != 1) return PV_ERR_SHAPE;
+  if (!policy->premature && !full_logits_dev) return PV_ERR_NULL;
+  if (policy->n_short < 0 || policy->n_short > PV_MAX_SHORT_CHUNKS || policy->kappa < 0 ||
+      policy->relaxed_count_min < 0)
+    return PV_ERR_SHAPE;
+  if (!(policy->eta >= 0.0) || !std::isfinite(policy->eta) || !(policy->rho >= 0.0) ||
+      std::isnan(policy->margin_chunk) || std::isnan(policy->margin_chunk_relaxed) ||
+      std::isnan(policy->margin_full) || std::isnan(policy->margin_full_relaxed))
+    return PV_ERR_SHAPE;
+  for (int i = 0; i < policy->n_short; ++i)
+    if (std::isnan(policy->margin_short[i])) return PV_ERR_SHAPE;
+  if (misaligned(plan_dev) || ((uintptr_t)logits_dev & 7u) || ((uintptr_t)full_logits_dev & 7u) ||
+      ((uintptr_t)out_dev & 15u))
+    return PV_ERR_ALIGN;
+  st = arch_ok_cached();
+  if (st != PV_OK) return st;
+  hipError_t e = launch_decide((const int32_t*)plan_dev, h, logits_dev, full_logits_dev, *policy,
+                               out_dev, (hipStream_t)stream);
+  if (e != hipSuccess) return hip_fail(e);
+  return PV_OK;
+}
+
 pv_status pv_plan_export(const pv_sizes* sizes, const void* plan_dev, int32_t* positions_dev,
                          int32_t* a_end_dev, int32_t* b_start_dev, int32_t* judge_row_dev,
                          void* stream) {

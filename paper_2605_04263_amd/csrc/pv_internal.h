@@ -69,6 +69,10 @@ hipError_t launch_plan_export(const int32_t* plan_dev, const PlanHeader& h, int3
                               int32_t* aend, int32_t* bstart, int32_t* judge, hipStream_t s);
 hipError_t launch_first_reject(const int32_t* plan_dev, const PlanHeader& h, const float* logits,
                                double thr, int mode, int32_t* out, hipStream_t s);
+hipError_t launch_decide(const int32_t* plan_dev, const PlanHeader& h, const float* logits,
+                         const float* full_logits, const pv_policy& pol, int32_t* out, hipStream_t s);
+hipError_t launch_judge_logits(const int32_t* plan_dev, const PlanHeader& h, const void* hidden,
+                               const void* w2, int hidden_size, float* logits, hipStream_t s);
 hipError_t launch_attn_f32(const int32_t* plan_dev, const PlanHeader& h, const float* q,
                            const float* k, const float* v, float* out, float* lse, int hq,
                            int hkv, int d, float scale, const RopeFreq& freq, bool rope,

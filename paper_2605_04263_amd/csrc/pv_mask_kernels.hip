@@ -285,4 +285,92 @@ hipError_t launch_first_reject(const int32_t* plan_dev, const PlanHeader& h, con
   return hipGetLastError();
 }
 
+// ---------------------------------------------------------------- decision policy
+// One thread per request; every comparison in fp64 on the margin l_C - l_I.
+__global__ __launch_bounds__(64) void k_decide(const int32_t* plan, PlanHeader h, const float* logits,
+                                               const float* full_logits, pv_policy pol,
+                                               int32_t* out) {
+  const int b = blockIdx.x * blockDim.x + threadIdx.x;
+  if (b >= h.batch) return;
+  const int s0 = plan[h.off_seg_start + b];
+  const int K = plan[h.off_nseg + b];
+  const int32_t* bounds = plan + h.off_bounds + s0;
+  int first = K, bad = 0, trailing = 0, below = 0, argmin = -1;
+  double dmin = 0.0;
+  for (int k = 0; k < K; ++k) {
+    const double d = (double)logits[2 * (s0 + k)] - (double)logits[2 * (s0 + k) + 1];
+    const bool ok = (d >= 0.0) && (d >= pol.margin_chunk);
+    if (ok) trailing = 0;
+    else { bad++; trailing++; if (first == K) first = k; }
+    if (d < pol.margin_chunk_relaxed) below++;
+    if (argmin < 0 || d < dmin) { argmin = k; dmin = d; }
+  }
+  const int k_star = first - 1;
+  const bool rejects = (K > 0 && (double)bad > pol.rho * (double)K) ||
+                       (pol.kappa > 0 && trailing >= pol.kappa);
+  const int m = (int)floor(fmax(0.0, (double)k_star + 1.0 - pol.eta));
+  const int l_star = m >= 1 ? bounds[m - 1] : 0;
+  const int handoff = l_star > 0 ? PV_LABEL_SM_LG : PV_LABEL_LG;
+  int label, stage, v_full = -1;
+  if (pol.premature) {
+    const bool abort = rejects || below >= pol.relaxed_count_min;
+    label = abort ? handoff : -1;
+    stage = abort ? 1 : 0;
+  } else {
+    const double df = (double)full_logits[2 * b] - (double)full_logits[2 * b + 1];
+    v_full = (df >= 0.0) && (df >= pol.margin_full);
+    if (v_full) { label = PV_LABEL_SM; stage = 2; }
+    else if (K >= 1 && K <= pol.n_short && df >= pol.margin_short[K - 1]) { label = PV_LABEL_SM; stage = 3; }
+    else if (df >= pol.margin_full_relaxed && below == 0) { label = PV_LABEL_SM; stage = 5; }
+    else { label = handoff; stage = 6; }
+  }
+  int32_t* o = out + 12 * b;
+  o[0] = label; o[1] = stage; o[2] = l_star; o[3] = k_star; o[4] = first; o[5] = bad;
+  o[6] = trailing; o[7] = rejects ? 1 : 0; o[8] = below; o[9] = v_full; o[10] = argmin; o[11] = K;
+}
+
+hipError_t launch_decide(const int32_t* plan_dev, const PlanHeader& h, const float* logits,
+                         const float* full_logits, const pv_policy& pol, int32_t* out, hipStream_t s) {
+  k_decide<<<dim3((h.batch + 63) / 64), dim3(64), 0, s>>>(plan_dev, h, logits, full_logits, pol, out);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------- judge logits
+// One wave per segment: lanes stride over the hidden dimension in 16-byte pieces, two fp32 dot
+// products, then a fixed-order butterfly reduction (bit-reproducible).
+__global__ __launch_bounds__(256) void k_judge_logits(const int32_t* plan, PlanHeader h,
+                                                      const uint16_t* hidden, const uint16_t* w2,
+                                                      int hs, float* logits) {
+  const int seg = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+  if (seg >= h.total_segments) return;
+  const int64_t row = plan[h.off_judge + seg];
+  const uint4* hp = reinterpret_cast<const uint4*>(hidden + row * hs);
+  const uint4* w0 = reinterpret_cast<const uint4*>(w2);
+  const uint4* w1 = reinterpret_cast<const uint4*>(w2 + hs);
+  float a0 = 0.0f, a1 = 0.0f;
+  for (int c = lane; c < hs / 8; c += 64) {
+    const uint4 x = hp[c], u = w0[c], v = w1[c];
+    const unsigned xs[4] = {x.x, x.y, x.z, x.w}, us[4] = {u.x, u.y, u.z, u.w}, vs[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const float xl = __uint_as_float(xs[e] << 16), xh = __uint_as_float(xs[e] & 0xffff0000u);
+      a0 = fmaf(xl, __uint_as_float(us[e] << 16), a0);
+      a0 = fmaf(xh, __uint_as_float(us[e] & 0xffff0000u), a0);
+      a1 = fmaf(xl, __uint_as_float(vs[e] << 16), a1);
+      a1 = fmaf(xh, __uint_as_float(vs[e] & 0xffff0000u), a1);
+    }
+  }
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) { a0 += __shfl_xor(a0, off); a1 += __shfl_xor(a1, off); }
+  if (lane == 0) { logits[2 * seg] = a0; logits[2 * seg + 1] = a1; }
+}
+
+hipError_t launch_judge_logits(const int32_t* plan_dev, const PlanHeader& h, const void* hidden,
+                               const void* w2, int hidden_size, float* logits, hipStream_t s) {
+  if (h.total_segments == 0) return hipSuccess;
+  k_judge_logits<<<dim3((h.total_segments + 3) / 4), dim3(256), 0, s>>>(
+      plan_dev, h, (const uint16_t*)hidden, (const uint16_t*)w2, hidden_size, logits);
+  return hipGetLastError();
+}
+
 }  // namespace pv

@@ -130,3 +130,36 @@ def test_launch_calls_reject_bad_arguments_before_touching_the_gpu():
     assert L.pv_first_reject(C.byref(s), None, fake, 0.0, 0, fake, None) == pv.PV_ERR_NULL
     assert L.pv_plan_export(C.byref(s), None, None, None, None, None, None) == pv.PV_ERR_NULL
     assert L.pv_profile_read(None) == pv.PV_ERR_NULL
+
+
+def test_policy_calls_reject_bad_arguments_before_touching_the_gpu():
+    p = pv.make_problem([4], [16], [2], [3], [5, 9])
+    st, s = q(p, 8, 2, 128)
+    assert st == pv.PV_OK
+    fake = 0x1000
+    L = pv.lib
+    pol = pv.make_policy(4.0, 2.0, 6.0, 3.0, [3.0, 3.0], 0.3, 2, 0.0)
+    dec = lambda **kw: L.pv_decide(C.byref(s), kw.get("plan", fake), kw.get("lg", fake), kw.get("full", fake),
+                                   C.byref(kw["pol"]) if kw.get("pol") is not None else None,
+                                   kw.get("out", fake), None)
+    assert dec(pol=None) == pv.PV_ERR_NULL
+    assert dec(pol=pol, lg=None) == pv.PV_ERR_NULL
+    assert dec(pol=pol, full=None) == pv.PV_ERR_NULL              # full-answer logits needed outside premature mode
+    assert dec(pol=pol, out=fake + 4) == pv.PV_ERR_ALIGN
+    bad = pv.make_policy(4.0, 2.0, 6.0, 3.0, [3.0], 0.3, -1, 0.0)
+    assert dec(pol=bad) == pv.PV_ERR_SHAPE
+    bad = pv.make_policy(4.0, 2.0, 6.0, 3.0, [3.0], 0.3, 2, -0.5)
+    assert dec(pol=bad) == pv.PV_ERR_SHAPE
+    bad = pv.make_policy(float("nan"), 2.0, 6.0, 3.0, [3.0], 0.3, 2, 0.0)
+    assert dec(pol=bad) == pv.PV_ERR_SHAPE
+    bad = pv.make_policy(4.0, 2.0, 6.0, 3.0, [3.0], 0.3, 2, 0.0)
+    bad.n_short = 9
+    assert dec(pol=bad) == pv.PV_ERR_SHAPE
+
+    jl = lambda **kw: L.pv_judge_logits(C.byref(s), kw.get("plan", fake), kw.get("h", fake), kw.get("w", fake),
+                                        kw.get("hs", 64), kw.get("out", fake), None)
+    assert jl(h=None) == pv.PV_ERR_NULL
+    assert jl(hs=60) == pv.PV_ERR_SHAPE
+    assert jl(hs=0) == pv.PV_ERR_SHAPE
+    assert jl(w=fake + 2) == pv.PV_ERR_ALIGN
+    assert jl(plan=None) == pv.PV_ERR_NULL
