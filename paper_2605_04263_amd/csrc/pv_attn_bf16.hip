@@ -496,23 +496,37 @@ __global__ __launch_bounds__(G * 64, 2) __attribute__((amdgpu_waves_per_eu(2))) 
   }
 
   // ---- pipeline prologue: P(0), S(1), K operand of step 2, V operand of step 0
-#pragma unroll
-  for (int s = NK0; s < NS; ++s) stage_k(s);
-#pragma unroll
-  for (int s = 0; s < NS; ++s) stage_v(s);
-  // K of the first steps (staged before the Q tile) must have landed; what was issued just now
-  // may still be in flight
-  if constexpr (NK0 >= 2)
-    wait_slots(std::integral_constant<int, 2 * NS - NK0>{},
-               min(NS, n_steps) + min(max(n_steps - NK0, 0), NS - NK0));
-  else
-    __builtin_amdgcn_s_waitcnt(0x0f70);
-  __builtin_amdgcn_s_barrier();        // not __syncthreads(): that would wait for the loads in flight
   f32x16 sA, sB;           // score tiles, alternating roles from step to step
   unsigned pA[8], pB[8];   // probability tiles (bf16 pairs), likewise
-  load_k(0);
-  wait_kv();
-  qk(sA);                                            // S(0)
+  // the slots that could not be staged before the Q tile: K(NK0 ..), then all of V^T
+  constexpr int NL = 2 * NS - NK0;
+  auto stage_late = [&](auto i) {
+    constexpr int I = decltype(i)::value;
+    if constexpr (I < NS - NK0) stage_k(NK0 + I);
+    else if constexpr (I < NL) stage_v(I - (NS - NK0));
+  };
+  if constexpr (NK0 >= 2) {
+    // K of steps 0 and 1 has landed (every wave waited for its loads before the barriers of the Q
+    // tile), so S(0) starts right away and the late slots are staged between its MFMAs.
+    load_k(0);
+    wait_kv();
+#pragma unroll
+    for (int r = 0; r < 16; ++r) sA[r] = 0.0f;
+    static_for<0, KT>([&](auto t) {
+      constexpr int T = decltype(t)::value;
+      sA = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[T], qf[T], sA, 0, 0, 0);
+      static_for<0, (NL + KT - 1) / KT>([&](auto m) {
+        stage_late(std::integral_constant<int, T + decltype(m)::value * KT>{});
+      });
+    });
+  } else {
+    static_for<0, NL>([&](auto i) { stage_late(i); });
+    __builtin_amdgcn_s_waitcnt(0x0f70);
+    __builtin_amdgcn_s_barrier();      // not __syncthreads(): that would wait for the loads in flight
+    load_k(0);
+    wait_kv();
+    qk(sA);                                          // S(0)
+  }
   __builtin_amdgcn_sched_barrier(0);
   load_k(min(1, last) % NS);
   if (0 >= tile.n_full * 64) apply_mask(sA, step_key0(0));
