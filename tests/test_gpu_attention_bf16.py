@@ -109,6 +109,30 @@ def test_group_sizes_long_rows(group, d):
     check_full(w)
 
 
+def random_problem(rng):
+    B = int(rng.integers(1, 4))
+    P = [int(x) for x in rng.integers(0, 90, B)]
+    T = [int(x) for x in rng.integers(1, 260, B)]
+    K = [int(x) for x in rng.integers(0, 6, B)]
+    S = [int(rng.choice([1, 2, 5, 16, 31, 32, 33, 47])) for _ in range(B)]
+    bounds = [sorted(int(x) for x in rng.integers(0, T[b] + 1, K[b])) for b in range(B)]
+    return wl.Problem(P, T, K, S, bounds)
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_random_problems(seed):
+    # seeded random shapes: ragged batches, segments shorter and longer than a tile, duplicate and zero
+    # boundaries, every group size, both head sizes, with and without rotation
+    rng = np.random.default_rng(7000 + seed)
+    pr = random_problem(rng)
+    group = int(rng.integers(1, 9))
+    hkv = int(rng.integers(1, 3))
+    d = int(rng.choice([64, 128]))
+    theta = float(rng.choice([0.0, 1e4, 5e5]))
+    w = wl.make_custom(pr, group * hkv, hkv, d, dtype=torch.bfloat16, rope_theta=theta, seed=7100 + seed)
+    check_full(w)
+
+
 def test_tiny_shape_in_bf16():
     t = wl.make("tiny", rope_theta=5e5)
     w = wl.make_custom(t.problem, 1, 1, 64, dtype=torch.bfloat16, rope_theta=5e5, seed=7)
