@@ -309,7 +309,8 @@ __global__ __launch_bounds__(G * 64, 2) __attribute__((amdgpu_waves_per_eu(2))) 
     bool done = false;
     static_for<0, MAXN>([&](auto c) {
       constexpr int v = MAXN - decltype(c)::value;
-      if constexpr (v * HPW <= 63) {
+      // (the counter has 6 bits: what stays in flight plus the loads of one more step must fit)
+      if constexpr (v * HPW + 2 * NREP <= 63) {
         if (!done && n >= v) { __builtin_amdgcn_s_waitcnt(vmcnt_imm(v * HPW)); done = true; }
       }
     });
@@ -417,7 +418,12 @@ __global__ __launch_bounds__(G * 64, 2) __attribute__((amdgpu_waves_per_eu(2))) 
   constexpr int CSCH = 32 * CSR;
   static_assert(QCH + CSCH <= 2 * NS * CH32, "Q tile and table must fit the rings");
   constexpr int QAREA0 = 2 * NS * CH32 - (QCH + CSCH);            // first chunk of the area
-  constexpr int NK0 = (QAREA0 / CH32) < NS ? (QAREA0 / CH32) : NS;  // K slots free from the start
+  // K slots staged together with the Q tile: those in front of the area, as far as the loads of
+  // one wave (Q tile, table, K slots) stay within the range of the 6-bit load counter
+  constexpr int QLOADS = QCH / 64 / G + (CSCH / 64 + G - 1) / G;
+  constexpr int NK0_FIT = (56 - QLOADS) / NREP > 0 ? (56 - QLOADS) / NREP : 0;
+  constexpr int NK0_FREE = (QAREA0 / CH32) < NS ? (QAREA0 / CH32) : NS;
+  constexpr int NK0 = NK0_FREE < NK0_FIT ? NK0_FREE : NK0_FIT;
   {
     const int rows_m1 = tile.rows - 1;
     const int64_t tok0 = (int64_t)tile.tok_base + tile.t0;
@@ -687,7 +693,7 @@ __global__ __launch_bounds__(G * 64, 2) __attribute__((amdgpu_waves_per_eu(2))) 
     // (step j+2) can be refilled.  Steps up to j+3 (K) and j+1 (V^T) must be visible; everything
     // issued after them may stay in flight:
     //   K(j+4) .. K(j+1+NS) and V^T(j+2) .. V^T(j+NS-1), as far as they exist and were issued.
-    if constexpr (STEADY && (2 * NS - 4) * HPW <= 63) {
+    if constexpr (STEADY && (2 * NS - 4) * HPW + 2 * NREP <= 63) {
       __builtin_amdgcn_s_waitcnt(vmcnt_imm((2 * NS - 4) * HPW));
     } else {
       const int cnt_k = min(NS - 2, j + 2), cnt_v = min(NS - 2, j);
