@@ -85,8 +85,12 @@ typedef struct {
 } pv_sizes;
 
 /* Host only: validates the problem and the head configuration and fills `out`.
- * Supported: head_dim 64 or 128, Hq a multiple of Hkv with Hq/Hkv <= 8, in_dtype PV_BF16
- * (MFMA path) or PV_F32 (debug path). */
+ * Supported: head_dim 64 or 128, Hq <= 1024 a multiple of Hkv with Hq/Hkv <= 8, in_dtype PV_BF16
+ * (MFMA path) or PV_F32 (debug path).  Limits (PV_ERR_SHAPE beyond them): B <= 2^20, N_b <= 2^24,
+ * total_tokens and padded_keys <= 2^27, so that every index of the plan fits int32.  A problem
+ * inside these limits whose kernels would still need a grid of 2^32 threads or more (for
+ * instance more than 2^24 work items times kv heads) is refused at launch time: PV_ERR_HIP with
+ * hipErrorInvalidConfiguration, nothing truncated. */
 pv_status pv_query_sizes(const pv_problem* problem, int32_t n_q_heads, int32_t n_kv_heads,
                          int32_t head_dim, int32_t in_dtype, pv_sizes* out);
 
@@ -193,11 +197,18 @@ pv_status pv_plan_export(const pv_sizes* sizes, const void* plan_dev, int32_t* p
                          int32_t* a_end_dev, int32_t* b_start_dev, int32_t* judge_row_dev,
                          void* stream);
 
-/* Profiling aid for benchmarks: when enabled, pv_masked_attention brackets its main attention
- * kernel with HIP events on the caller's stream.  pv_profile_read waits for the latest pair and
- * returns the kernel's duration in milliseconds (PV_ERR_SHAPE if nothing was recorded). */
+/* Profiling aid for benchmarks (one thread at a time): when enabled, pv_masked_attention brackets
+ * its main attention kernel with a pair of HIP events on the caller's stream, one pair per call out
+ * of a ring of PV_PROFILE_RING pairs, without waiting for anything.  Enabling restarts the count.
+ *   pv_profile_read      waits for the latest pair; the kernel's duration in milliseconds
+ *                        (PV_ERR_SHAPE if nothing was recorded).
+ *   pv_profile_read_all  waits for and returns the durations of the calls since enabling, oldest
+ *                        first: the last min(calls, PV_PROFILE_RING, capacity) of them into
+ *                        ms_host (host memory), their number into *n_out. */
+enum { PV_PROFILE_RING = 1024 };
 pv_status pv_profile_enable(int32_t on);
 pv_status pv_profile_read(float* main_kernel_ms);
+pv_status pv_profile_read_all(float* ms_host, int32_t capacity, int32_t* n_out);
 
 const char* pv_strerror(pv_status status);
 int32_t pv_last_hip_error(void);

@@ -76,8 +76,10 @@ def _load() -> C.CDLL:
                               C.c_void_p, C.c_void_p]
     lib.pv_profile_enable.argtypes = [C.c_int32]
     lib.pv_profile_read.argtypes = [P(C.c_float)]
+    lib.pv_profile_read_all.argtypes = [P(C.c_float), C.c_int32, P(C.c_int32)]
     for name in ("pv_query_sizes", "pv_build_mask", "pv_masked_attention", "pv_first_reject",
-                 "pv_plan_export", "pv_profile_enable", "pv_profile_read", "pv_last_hip_error",
+                 "pv_plan_export", "pv_profile_enable", "pv_profile_read", "pv_profile_read_all",
+                 "pv_last_hip_error",
                  "pv_judge_logits", "pv_decide"):
         getattr(lib, name).restype = C.c_int32
     lib.pv_strerror.argtypes = [C.c_int32]
@@ -132,6 +134,10 @@ def pv_query_sizes(problem: HostProblem, n_q_heads: int, n_kv_heads: int, head_d
 def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
     if t is None:
         return None
+    # the library dereferences these on the GPU of the current stream: host memory or another
+    # GPU's memory would fault there, so it is refused here
+    if not t.is_cuda or t.device.index != torch.cuda.current_device():
+        raise ValueError("tensor must live on the current GPU")
     if not t.is_contiguous():
         raise ValueError("tensor must be contiguous")
     return t.data_ptr()
@@ -246,6 +252,18 @@ def pv_profile_read() -> float:
     ms = C.c_float(0.0)
     _check(lib.pv_profile_read(C.byref(ms)), "pv_profile_read")
     return ms.value
+
+
+PV_PROFILE_RING = 1024
+
+
+def pv_profile_read_all() -> list:
+    """Main-kernel durations (ms) of the attention calls since profiling was enabled, oldest first
+    (the last PV_PROFILE_RING of them)."""
+    buf = (C.c_float * PV_PROFILE_RING)()
+    n = C.c_int32(0)
+    _check(lib.pv_profile_read_all(buf, PV_PROFILE_RING, C.byref(n)), "pv_profile_read_all")
+    return [buf[i] for i in range(n.value)]
 
 
 def margin_from_tau(tau: float) -> float:

@@ -10,8 +10,8 @@ namespace pv {
 
 static thread_local int32_t g_last_hip = 0;
 static bool g_profile = false;
-static hipEvent_t g_ev0 = nullptr, g_ev1 = nullptr;
-static bool g_ev_recorded = false;
+static hipEvent_t g_ev[PV_PROFILE_RING][2];     // created on first use, kept until the process ends
+static int64_t g_ev_calls = 0;                  // calls recorded since profiling was enabled
 
 static inline pv_status hip_fail(hipError_t e) {
   g_last_hip = (int32_t)e;
@@ -163,6 +163,10 @@ static pv_status check_sizes(const pv_sizes* s, PlanHeader* h) {
       s->tile_m != kTileM || s->tile_n != kTileN || s->padded_keys < s->total_tokens ||
       s->n_short_rows < 0 || s->n_short_rows > s->total_tokens)
     return PV_ERR_SHAPE;
+  // the limits pv_query_sizes enforces: every index and offset of the plan stays inside int32
+  if (s->batch > (1 << 20) || s->total_tokens > (1ll << 27) || s->padded_keys > (1ll << 27) ||
+      s->total_segments > s->total_tokens || s->n_q_tiles > s->total_tokens)
+    return PV_ERR_SHAPE;
   if (validate_heads(s->n_q_heads, s->n_kv_heads, s->head_dim, s->in_dtype) != PV_OK)
     return PV_ERR_SHAPE;
   plan_layout((int)s->batch, s->total_tokens, s->total_segments, s->n_q_tiles, s->padded_keys,
@@ -309,18 +313,19 @@ pv_status pv_masked_attention(const pv_sizes* sizes, const void* plan_dev, const
   } else {
     hipEvent_t ev0 = nullptr, ev1 = nullptr;
     if (g_profile) {
-      if (!g_ev0) {
-        e = hipEventCreate(&g_ev0);
+      hipEvent_t* pair = g_ev[g_ev_calls % PV_PROFILE_RING];
+      if (!pair[1]) {
+        e = hipEventCreate(&pair[0]);
         if (e != hipSuccess) return hip_fail(e);
-        e = hipEventCreate(&g_ev1);
+        e = hipEventCreate(&pair[1]);
         if (e != hipSuccess) return hip_fail(e);
       }
-      ev0 = g_ev0;
-      ev1 = g_ev1;
+      ev0 = pair[0];
+      ev1 = pair[1];
     }
     e = launch_attn_bf16((const int32_t*)plan_dev, h, q, k, v, out, lse, hq, hkv, d, out_dtype,
                          scale, freq, rope, (char*)workspace, wl, ev0, ev1, s);
-    if (e == hipSuccess && g_profile) g_ev_recorded = true;
+    if (e == hipSuccess && g_profile) ++g_ev_calls;
   }
   if (e != hipSuccess) return hip_fail(e);
   return PV_OK;
@@ -412,17 +417,37 @@ pv_status pv_plan_export(const pv_sizes* sizes, const void* plan_dev, int32_t* p
 
 pv_status pv_profile_enable(int32_t on) {
   g_profile = on != 0;
-  if (!g_profile) g_ev_recorded = false;
+  g_ev_calls = 0;
+  return PV_OK;
+}
+
+static pv_status profile_pair_ms(int64_t call, float* ms) {
+  hipEvent_t* pair = g_ev[call % PV_PROFILE_RING];
+  hipError_t e = hipEventSynchronize(pair[1]);
+  if (e != hipSuccess) return hip_fail(e);
+  e = hipEventElapsedTime(ms, pair[0], pair[1]);
+  if (e != hipSuccess) return hip_fail(e);
   return PV_OK;
 }
 
 pv_status pv_profile_read(float* main_kernel_ms) {
   if (!main_kernel_ms) return PV_ERR_NULL;
-  if (!g_profile || !g_ev_recorded) return PV_ERR_SHAPE;
-  hipError_t e = hipEventSynchronize(g_ev1);
-  if (e != hipSuccess) return hip_fail(e);
-  e = hipEventElapsedTime(main_kernel_ms, g_ev0, g_ev1);
-  if (e != hipSuccess) return hip_fail(e);
+  if (!g_profile || g_ev_calls == 0) return PV_ERR_SHAPE;
+  return profile_pair_ms(g_ev_calls - 1, main_kernel_ms);
+}
+
+pv_status pv_profile_read_all(float* ms_host, int32_t capacity, int32_t* n_out) {
+  if (!ms_host || !n_out) return PV_ERR_NULL;
+  if (capacity < 0) return PV_ERR_SHAPE;
+  *n_out = 0;
+  if (!g_profile) return PV_ERR_SHAPE;
+  int64_t n = g_ev_calls < PV_PROFILE_RING ? g_ev_calls : PV_PROFILE_RING;
+  if (n > capacity) n = capacity;
+  for (int64_t i = 0; i < n; ++i) {
+    pv_status st = profile_pair_ms(g_ev_calls - n + i, &ms_host[i]);
+    if (st != PV_OK) return st;
+  }
+  *n_out = (int32_t)n;
   return PV_OK;
 }
 

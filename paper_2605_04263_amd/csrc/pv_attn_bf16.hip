@@ -819,7 +819,8 @@ static hipError_t launch_main(const int32_t* plan, const PlanHeader& h, const ui
                               const uint16_t* krot, const uint16_t* vt, const float2* cs, void* out,
                               float* lse, int hq, int hkv, float qscale, bool rope, bool out_f32,
                               hipStream_t s) {
-  const dim3 grid((unsigned)((int64_t)h.n_q_tiles * hkv));
+  dim3 grid;
+  if (!grid_1d((int64_t)h.n_q_tiles * hkv, G * 64, &grid)) return hipErrorInvalidConfiguration;
   if (rope)
     k_attn_bf16<D, G, true><<<grid, dim3(G * 64), 0, s>>>(plan, h, q, krot, vt, cs, out, lse, hq, hkv,
                                                           qscale, rope, out_f32);
@@ -855,7 +856,9 @@ hipError_t launch_attn_bf16(const int32_t* plan_dev, const PlanHeader& h, const 
   const uint16_t* kv = reinterpret_cast<const uint16_t*>(v);
   hipError_t e;
   {
-    const dim3 grid((unsigned)((h.padded_keys / 16) * ((hkv + 1) / 2) + h.n_short_rows * hkv));
+    dim3 grid;
+    if (!grid_1d((int64_t)(h.padded_keys / 16) * ((hkv + 1) / 2) + (int64_t)h.n_short_rows * hkv, 256, &grid))
+      return hipErrorInvalidConfiguration;
     ShortRowArgs sr;
     sr.q = kq; sr.out = out; sr.lse = lse; sr.hq = hq; sr.scale = scale; sr.out_f32 = out_dtype == PV_F32;
     if (d == 64) k_prep_kv<64><<<grid, dim3(256), 0, s>>>(plan_dev, h, kk, kv, freq, cs, hkv, rope, krot, vt, sr);

@@ -97,21 +97,23 @@ hipError_t launch_attn_f32(const int32_t* plan_dev, const PlanHeader& h, const f
   float* k_rot = reinterpret_cast<float*>(ws + wl.off_krot);
   const int half = d / 2;
   hipError_t e;
+  dim3 grid;
   if (rope) {
     const int64_t n = (int64_t)h.total_tokens * half;
-    k_rope_table<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s>>>(plan_dev, h, freq, half, cs);
+    if (!grid_1d((n + 255) / 256, 256, &grid)) return hipErrorInvalidConfiguration;
+    k_rope_table<<<grid, dim3(256), 0, s>>>(plan_dev, h, freq, half, cs);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
   }
   {
     const int64_t n = (int64_t)h.total_tokens * hkv * half;
-    k_rotate_k_f32<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s>>>(k, cs, hkv, d,
-                                                                          h.total_tokens, k_rot, rope);
+    if (!grid_1d((n + 255) / 256, 256, &grid)) return hipErrorInvalidConfiguration;
+    k_rotate_k_f32<<<grid, dim3(256), 0, s>>>(k, cs, hkv, d, h.total_tokens, k_rot, rope);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
   }
   const int64_t n = (int64_t)h.total_tokens * hq;
-  const dim3 grid((unsigned)((n + 63) / 64));
+  if (!grid_1d((n + 63) / 64, 64, &grid)) return hipErrorInvalidConfiguration;
   if (d == 64)
     k_attn_f32<64><<<grid, dim3(64), 0, s>>>(plan_dev, h, q, k_rot, v, out, lse, hq, hkv, scale, cs, rope);
   else

@@ -38,6 +38,14 @@ struct PlanHeader {
 };
 static_assert(sizeof(PlanHeader) == 32 * 4, "PlanHeader must be 32 ints");
 
+// One-dimensional grid of `blocks` workgroups of `threads` threads.  A launch may not span 2^32
+// threads or more: a grid that large is reported as an error and never truncated.
+inline bool grid_1d(int64_t blocks, int threads, dim3* grid) {
+  if (blocks < 1 || blocks * threads > 0xffffffffll) return false;
+  *grid = dim3((unsigned)blocks);
+  return true;
+}
+
 // One query tile of the work list (8 ints).
 struct QTile {
   int32_t tok_base;    // first packed row of the request

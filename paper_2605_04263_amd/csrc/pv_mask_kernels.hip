@@ -229,7 +229,9 @@ hipError_t launch_plan_kernels(int32_t* plan_dev, const PlanHeader& h, const int
     if (e != hipSuccess) return e;
   }
   if (dense_mask) {
-    k_dense_mask<<<dim3(h.total_tokens), dim3(256), 0, s>>>(plan_dev, h, dense_mask);
+    dim3 grid;
+    if (!grid_1d(h.total_tokens, 256, &grid)) return hipErrorInvalidConfiguration;
+    k_dense_mask<<<grid, dim3(256), 0, s>>>(plan_dev, h, dense_mask);
     e = hipGetLastError();
   }
   return e;
@@ -368,7 +370,9 @@ __global__ __launch_bounds__(256) void k_judge_logits(const int32_t* plan, PlanH
 hipError_t launch_judge_logits(const int32_t* plan_dev, const PlanHeader& h, const void* hidden,
                                const void* w2, int hidden_size, float* logits, hipStream_t s) {
   if (h.total_segments == 0) return hipSuccess;
-  k_judge_logits<<<dim3((h.total_segments + 3) / 4), dim3(256), 0, s>>>(
+  dim3 grid;
+  if (!grid_1d(((int64_t)h.total_segments + 3) / 4, 256, &grid)) return hipErrorInvalidConfiguration;
+  k_judge_logits<<<grid, dim3(256), 0, s>>>(
       plan_dev, h, (const uint16_t*)hidden, (const uint16_t*)w2, hidden_size, logits);
   return hipGetLastError();
 }

@@ -121,6 +121,14 @@ def test_launch_calls_reject_bad_arguments_before_touching_the_gpu():
     tampered = pv.PvSizes.from_buffer_copy(s)
     tampered.plan_bytes += 16
     assert att(s=tampered) == pv.PV_ERR_SHAPE
+    # a hand-made sizes struct beyond the documented limits is refused even if its plan size agrees
+    huge = pv.PvSizes.from_buffer_copy(s)
+    huge.total_tokens = (1 << 27) + 64
+    huge.padded_keys = (1 << 27) + 64
+    assert att(s=huge) == pv.PV_ERR_SHAPE
+    many = pv.PvSizes.from_buffer_copy(s)
+    many.total_segments = s.total_tokens + 1
+    assert att(s=many) == pv.PV_ERR_SHAPE
     st, s32 = q(p, 8, 2, 128, pv.PV_F32)
     assert att(s=s32, odt=pv.PV_BF16, wsb=s32.attn_workspace_bytes) == pv.PV_ERR_DTYPE   # fp32 in needs fp32 out
 

@@ -186,3 +186,24 @@ def test_work_list_multi_kernel_plan():
     pr = wl.Problem(P, T, K, S, bounds)
     assert pr.total_tokens > 8192
     check_work_list(pr)
+
+
+def test_binding_refuses_host_and_strided_tensors():
+    # the binding passes raw addresses to kernels: anything that is not contiguous memory of the
+    # current GPU must be stopped in Python, before a launch
+    w = wl.make("tiny")
+    ver = gc.make_verifier(pv, w)
+    ver.build_mask()
+    dev = ver.device
+    q, k, v = w.q.to(dev), w.k.to(dev), w.v.to(dev)
+    out = torch.empty_like(q)
+    with pytest.raises(ValueError):
+        ver.attention(w.q, k, v, out=out)                                   # q in host memory
+    with pytest.raises(ValueError):
+        ver.attention(q, k, v, out=torch.empty(q.shape, dtype=q.dtype))     # out in host memory
+    wide = torch.empty(q.shape[0], q.shape[1], 2 * q.shape[2], dtype=q.dtype, device=dev)
+    with pytest.raises(ValueError):
+        ver.attention(q, k, v, out=wide[:, :, :q.shape[2]])                 # strided view
+    with pytest.raises(ValueError):
+        ver.first_reject(torch.zeros(ver.sizes.total_segments, 2), 0.0)     # logits in host memory
+    torch.cuda.synchronize()
