@@ -572,7 +572,7 @@ __global__ __launch_bounds__(G * 64, 2) __attribute__((amdgpu_waves_per_eu(2))) 
     const bool have1 = !decltype(last_of_pair)::value || j + 1 <= last;
     if (have1) {
       const int key0 = step_key0(j + 1);
-      if (key0 >= tile.n_full * 64) apply_mask(s_in, key0);
+      if (__builtin_expect(key0 >= tile.n_full * 64, 0)) apply_mask(s_in, key0);
     }
     const int slot_ks = sj + 2 >= NS ? sj + 2 - NS : sj + 2;   // (j + 2) % NS
     const bf16x8 pfa = as_bf16x8(make_uint4(p_in[0], p_in[1], p_in[2], p_in[3]));
@@ -729,7 +729,7 @@ __global__ __launch_bounds__(G * 64, 2) __attribute__((amdgpu_waves_per_eu(2))) 
     asm volatile("" : "+v"(rs));                      // the row sum belongs to this block
     __builtin_amdgcn_sched_barrier(0);
     if (have1) {
-      if (out_of_window(rs)) rs = recentre(s_in, p_out);
+      if (__builtin_expect(out_of_window(rs), 0)) rs = recentre(s_in, p_out);
       l_run += rs;
     }
     slot_v = (j + 2 <= last) ? (slot_v + 1 == NS ? 0 : slot_v + 1) : slot_v;
