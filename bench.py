@@ -204,6 +204,7 @@ def main() -> int:
                          "attention_main_kernel": kernel_ms, "step_with_kernel_events": ms_per_step_events},
         "after_step_ms": {"pv_judge_logits_h4096": t_judge, "pv_decide": t_decide},
         "attn_tflops": eff_flops / (t_attn * 1e-3) / 1e12,
+        "max_abs_output": float(out.float().abs().max()),   # bf16 output spacing grows with |o|
         "roofline": {"bound": "mfma", "kernel": "k_attn_bf16", "achieved": achieved,
                      "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": traffic},

@@ -17,6 +17,8 @@ calibration", "Parallel partial verify", "Adopted-prefix length"):
                     stand-alone run of (prefix, suffix).
 * `rope`            rotary embedding, half-split pairing.
 * `attention`       softmax(mask(Q K^T * scale)) V for one request, no tiling.
+* `*_interleaved`   the same pass in the packing of "Parallel partial verify": every suffix
+                    copy (End slot) directly after its chunk instead of after the draft.
 * `first_reject`    two-way confidence verdicts (Eq. for p_2w), the last-correct
                     index k* ("Parallel partial verify"), the adopted length L*
                     (Eq. "adopted", with rollback eta = 0 generalised to arbitrary
@@ -95,6 +97,77 @@ def judge_rows(P: int, T: int, S: int, K: int) -> np.ndarray:
     return np.array([P + T + (k + 1) * S - 1 for k in range(K)], dtype=np.int64)
 
 
+# --------------------------------------------------------------------------- interleaved packing
+
+LAYOUT_APPENDED, LAYOUT_INTERLEAVED = 0, 1
+
+
+def interleaved_tokens(P: int, T: int, S: int, boundaries: Sequence[int]):
+    """The packed prompt of "Parallel partial verify", token by token:
+    prefix | C_1 | End_1 | C_2 | End_2 | ... | C_K | End_K | (draft tokens after the last boundary),
+    where chunk C_k holds the draft tokens between boundary k-1 and boundary k and End_k is the
+    k-th copy of the S-token judge suffix.  Returns a list of tuples
+      ('q', i)        prefix token i,
+      ('c', k, t)     draft token t, a member of chunk k (k = K for the tail after the last End),
+      ('e', k, a)     token a of End slot k."""
+    toks = [('q', i) for i in range(P)]
+    prev = 0
+    for k, p in enumerate(boundaries):
+        toks += [('c', k, t) for t in range(prev, p)]
+        toks += [('e', k, a) for a in range(S)]
+        prev = p
+    toks += [('c', len(boundaries), t) for t in range(prev, T)]
+    return toks
+
+
+def dense_mask_interleaved(P: int, T: int, S: int, boundaries: Sequence[int],
+                           rows: Optional[Sequence[int]] = None) -> np.ndarray:
+    """The mask of the interleaved packing ("Parallel partial verify"): an End slot attends to the
+    question prefix, to its own prefix C_1..C_k, causally to itself, and to nothing else (no other
+    End slot, no later chunk).  Prefix and chunk tokens are the ordinary causal sequence
+    prefix + draft: a chunk token attends to the prefix and to the draft tokens up to itself, and
+    never to an End slot (End slots are insertions the draft must not see)."""
+    toks = interleaved_tokens(P, T, S, boundaries)
+    N = len(toks)
+    if rows is None:
+        rows = range(N)
+    kind = np.array([t[0] for t in toks])
+    index = np.array([t[1] for t in toks])           # chunk or slot number (prefix: token index)
+    j = np.arange(N)
+    key_prefix, key_chunk, key_end = kind == 'q', kind == 'c', kind == 'e'
+    M = np.zeros((len(rows), N), dtype=np.uint8)
+    for r, i in enumerate(rows):
+        not_later = j <= i                           # nothing attends forward
+        if kind[i] == 'e':
+            k = index[i]
+            visible = key_prefix | (key_chunk & (index <= k)) | (key_end & (index == k))
+        else:                                        # prefix or chunk token: the plain causal sequence
+            visible = key_prefix | key_chunk
+        M[r] = visible & not_later
+    return M
+
+
+def positions_interleaved(P: int, T: int, S: int, boundaries: Sequence[int]) -> np.ndarray:
+    """Rotary positions in the interleaved packing: prefix and draft tokens keep the positions of
+    the plain sequence prefix + draft; End slot k continues from the end of the prefix it judges."""
+    pos = []
+    for tok in interleaved_tokens(P, T, S, boundaries):
+        if tok[0] == 'q':
+            pos.append(tok[1])
+        elif tok[0] == 'c':
+            pos.append(P + tok[2])
+        else:
+            pos.append(P + boundaries[tok[1]] + tok[2])
+    return np.asarray(pos, dtype=np.int64)
+
+
+def judge_rows_interleaved(P: int, T: int, S: int, boundaries: Sequence[int]) -> np.ndarray:
+    """Row of the last token of every End slot."""
+    toks = interleaved_tokens(P, T, S, boundaries)
+    where = {(t[1]): i for i, t in enumerate(toks) if t[0] == 'e' and t[2] == S - 1}
+    return np.asarray([where[k] for k in range(len(boundaries))], dtype=np.int64)
+
+
 # --------------------------------------------------------------------------- rotary
 
 def rope(x: np.ndarray, pos: np.ndarray, theta: float) -> np.ndarray:
@@ -151,24 +224,29 @@ def attention(q: np.ndarray, k: np.ndarray, v: np.ndarray, mask: np.ndarray,
 
 def masked_attention(prompt_len, draft_len, num_segments, segment_len, boundaries,
                      q: np.ndarray, k: np.ndarray, v: np.ndarray, rope_theta: float = 0.0,
-                     scale: Optional[float] = None, rows_per_request=None, return_lse: bool = False):
+                     scale: Optional[float] = None, rows_per_request=None, return_lse: bool = False,
+                     layout: int = LAYOUT_APPENDED):
     """The packed pass: every request of the batch, tokens concatenated request after request.
 
     `boundaries` is a list of per-request lists.  q/k/v hold the same values the GPU is
     given, widened to fp64.  `rows_per_request[b]` (optional) restricts request b to the
     listed local query rows; the outputs are then concatenated in that order.
+    `layout` selects the packing of a request's tokens: suffix copies appended after the draft,
+    or interleaved after their chunks ("Parallel partial verify").
     """
+    mask_fn = dense_mask_interleaved if layout == LAYOUT_INTERLEAVED else dense_mask
+    pos_fn = positions_interleaved if layout == LAYOUT_INTERLEAVED else positions
     outs, lses = [], []
     start = 0
     for b in range(len(prompt_len)):
         P, T, K, S = prompt_len[b], draft_len[b], num_segments[b], segment_len[b]
         N = P + T + K * S
         rows = None if rows_per_request is None else rows_per_request[b]
-        pos = positions(P, T, S, boundaries[b])
+        pos = pos_fn(P, T, S, boundaries[b])
         qb = rope(np.asarray(q[start:start + N], dtype=np.float64), pos, rope_theta)
         kb = rope(np.asarray(k[start:start + N], dtype=np.float64), pos, rope_theta)
         vb = np.asarray(v[start:start + N], dtype=np.float64)
-        M = dense_mask(P, T, S, boundaries[b], rows)
+        M = mask_fn(P, T, S, boundaries[b], rows)
         o, l = attention(qb, kb, vb, M, scale, rows, return_lse=True)
         outs.append(o)
         lses.append(l)

@@ -29,6 +29,7 @@ class Problem:
     num_segments: List[int]
     segment_len: List[int]
     boundaries: List[List[int]]          # per request, non-decreasing, 0 <= p <= T
+    layout: int = 0                      # 0: segments appended after the draft; 1: each segment right after its chunk
 
     @property
     def batch(self) -> int:
