@@ -12,7 +12,12 @@
  * Conventions shared by every entry point
  *   Layout     Packed variable length: the tokens of all requests are concatenated; request b
  *              owns rows [tok_start[b], tok_start[b+1]) in the order
- *              [prompt | draft | segment_0 | ... | segment_{K-1}].  Q and O are
+ *              [prompt | draft | segment_0 | ... | segment_{K-1}] (PV_LAYOUT_APPENDED), or with
+ *              every segment directly after the draft tokens it judges,
+ *              [prompt | draft[0:p_0] | segment_0 | draft[p_0:p_1] | segment_1 | ... | draft[p_{K-1}:T]]
+ *              (PV_LAYOUT_INTERLEAVED, the packing of appendix "Parallel partial verify").  Both
+ *              hold the same tokens with the same visibility and positions; only the row order of
+ *              the caller's tensors differs.  Q and O are
  *              [total_tokens][Hq][D], K and V are [total_tokens][Hkv][D], innermost contiguous,
  *              base pointers 16-byte aligned.
  *   Memory     "host" pointers are ordinary CPU memory read only during the call.  "device"
@@ -50,6 +55,7 @@ enum {
 };
 
 enum { PV_BF16 = 0, PV_F32 = 1 };
+enum { PV_LAYOUT_APPENDED = 0, PV_LAYOUT_INTERLEAVED = 1 };
 
 /* Rows that see at most this many keys (the first tokens of a request, or a segment whose prefix is
  * almost empty) are evaluated in plain fp32 by the bf16 path: with so few terms the bf16 rounding
@@ -65,6 +71,7 @@ typedef struct {
   const int32_t* segment_len;    /* [B]  S_b >= 1   (same for all segments of a request) */
   const int32_t* boundaries;     /* [sum K_b] p_k = number of draft tokens segment k sees;
                                     per request non-decreasing and 0 <= p_k <= T_b */
+  int32_t layout;                /* PV_LAYOUT_APPENDED or PV_LAYOUT_INTERLEAVED (whole batch) */
 } pv_problem;
 
 /* Sizes derived from a pv_problem; filled by pv_query_sizes, passed back to the other calls. */
@@ -81,7 +88,7 @@ typedef struct {
   int32_t n_q_heads, n_kv_heads, head_dim, in_dtype;
   int32_t tile_m, tile_n;        /* query tokens per work item, keys per tile */
   int32_t n_short_rows;          /* rows with at most PV_SHORT_ROW_KEYS visible keys (see below) */
-  int32_t reserved;
+  int32_t layout;                /* the problem's layout */
 } pv_sizes;
 
 /* Host only: validates the problem and the head configuration and fills `out`.
@@ -191,8 +198,10 @@ pv_status pv_decide(const pv_sizes* sizes, const void* plan_dev, const float* lo
                     void* stream);
 
 /* Copies of the plan's per-token / per-segment arrays for inspection (device to device, on
- * `stream`): positions, a_end, b_start are int32 [total_tokens]; judge_row is int32
- * [total_segments] (row index into the packed token dimension).  Any output may be NULL. */
+ * `stream`): positions, a_end, b_start are int32 [total_tokens], one entry per row of the caller's
+ * tensors; judge_row is int32 [total_segments] (row of the caller's tensors).  The row descriptor
+ * (a_end, b_start) counts keys in the appended order of the request whatever the layout.  Any
+ * output may be NULL. */
 pv_status pv_plan_export(const pv_sizes* sizes, const void* plan_dev, int32_t* positions_dev,
                          int32_t* a_end_dev, int32_t* b_start_dev, int32_t* judge_row_dev,
                          void* stream);

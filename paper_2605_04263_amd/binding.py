@@ -21,6 +21,7 @@ PV_OK = 0
 PV_ERR_NULL, PV_ERR_SHAPE, PV_ERR_BOUNDARY, PV_ERR_WORKSPACE = -1, -2, -3, -4
 PV_ERR_ALIGN, PV_ERR_DTYPE, PV_ERR_ARCH, PV_ERR_HIP = -5, -6, -7, -8
 PV_BF16, PV_F32 = 0, 1
+PV_LAYOUT_APPENDED, PV_LAYOUT_INTERLEAVED = 0, 1
 
 
 class PvProblem(C.Structure):
@@ -29,7 +30,8 @@ class PvProblem(C.Structure):
                 ("draft_len", C.POINTER(C.c_int32)),
                 ("num_segments", C.POINTER(C.c_int32)),
                 ("segment_len", C.POINTER(C.c_int32)),
-                ("boundaries", C.POINTER(C.c_int32))]
+                ("boundaries", C.POINTER(C.c_int32)),
+                ("layout", C.c_int32)]
 
 
 class PvSizes(C.Structure):
@@ -39,7 +41,7 @@ class PvSizes(C.Structure):
                 ("attn_workspace_bytes", C.c_int64),
                 ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32),
                 ("in_dtype", C.c_int32), ("tile_m", C.c_int32), ("tile_n", C.c_int32),
-                ("n_short_rows", C.c_int32), ("reserved", C.c_int32)]
+                ("n_short_rows", C.c_int32), ("layout", C.c_int32)]
 
 
 PV_MAX_SHORT_CHUNKS = 8
@@ -117,9 +119,10 @@ class HostProblem:
 
 
 def make_problem(prompt_len: Sequence[int], draft_len: Sequence[int], num_segments: Sequence[int],
-                 segment_len: Sequence[int], boundaries: Sequence[int]) -> HostProblem:
+                 segment_len: Sequence[int], boundaries: Sequence[int],
+                 layout: int = PV_LAYOUT_APPENDED) -> HostProblem:
     arrs = tuple(_i32(list(x)) for x in (prompt_len, draft_len, num_segments, segment_len, boundaries))
-    s = PvProblem(len(prompt_len), *[C.cast(a, C.POINTER(C.c_int32)) for a in arrs])
+    s = PvProblem(len(prompt_len), *[C.cast(a, C.POINTER(C.c_int32)) for a in arrs], layout)
     return HostProblem(s, arrs)
 
 
@@ -276,8 +279,8 @@ class Verifier:
 
     def __init__(self, prompt_len, draft_len, num_segments, segment_len, boundaries_flat,
                  n_q_heads: int, n_kv_heads: int, head_dim: int, dtype: torch.dtype,
-                 device: str = "cuda:0", dense_mask: bool = False):
-        self.problem = make_problem(prompt_len, draft_len, num_segments, segment_len, boundaries_flat)
+                 device: str = "cuda:0", dense_mask: bool = False, layout: int = PV_LAYOUT_APPENDED):
+        self.problem = make_problem(prompt_len, draft_len, num_segments, segment_len, boundaries_flat, layout)
         in_dtype = PV_F32 if dtype == torch.float32 else PV_BF16
         self.sizes = pv_query_sizes(self.problem, n_q_heads, n_kv_heads, head_dim, in_dtype)
         self.device = torch.device(device)

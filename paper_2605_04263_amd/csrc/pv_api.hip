@@ -21,7 +21,7 @@ static inline pv_status hip_fail(hipError_t e) {
 static inline int64_t align_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
 
 void plan_layout(int batch, int64_t total_tokens, int64_t total_segments, int64_t n_q_tiles,
-                 int64_t padded_keys, int64_t n_short_rows, PlanHeader* h) {
+                 int64_t padded_keys, int64_t n_short_rows, int layout, PlanHeader* h) {
   std::memset(h, 0, sizeof(*h));
   h->magic = kPlanMagic;
   h->batch = batch;
@@ -32,6 +32,7 @@ void plan_layout(int batch, int64_t total_tokens, int64_t total_segments, int64_
   h->tile_n = kTileN;
   h->padded_keys = (int32_t)padded_keys;
   h->n_short_rows = (int32_t)n_short_rows;
+  h->layout = layout;
   int64_t o = sizeof(PlanHeader) / 4;
   auto take = [&](int64_t n) { int64_t r = o; o = align_up(o + n, 4); return (int32_t)r; };
   h->off_prompt = take(batch);
@@ -52,6 +53,7 @@ void plan_layout(int batch, int64_t total_tokens, int64_t total_segments, int64_
   h->off_judge = take(total_segments);
   h->off_tiles = take(n_q_tiles * 8);
   h->off_work = take(n_q_tiles * 8);
+  h->off_map = layout == PV_LAYOUT_INTERLEAVED ? take(total_tokens) : 0;
   h->total_ints = (int32_t)o;
 }
 
@@ -93,6 +95,7 @@ static void for_each_short_row(int64_t P, int64_t T, int64_t K, int64_t S, const
 static pv_status validate_problem(const pv_problem* p, Totals* t) {
   if (!p) return PV_ERR_NULL;
   if (p->batch < 1 || p->batch > (1 << 20)) return PV_ERR_SHAPE;
+  if (p->layout != PV_LAYOUT_APPENDED && p->layout != PV_LAYOUT_INTERLEAVED) return PV_ERR_SHAPE;
   if (!p->prompt_len || !p->draft_len || !p->num_segments || !p->segment_len) return PV_ERR_NULL;
   int64_t nseg = 0;
   for (int b = 0; b < p->batch; ++b) {
@@ -143,8 +146,9 @@ static void fill_sizes(const pv_problem* p, const Totals& t, int hq, int hkv, in
   s->n_q_tiles = t.q_tiles;
   s->padded_keys = t.padded_keys;
   PlanHeader h;
-  plan_layout(p->batch, t.tokens, t.segments, t.q_tiles, t.padded_keys, t.short_rows, &h);
+  plan_layout(p->batch, t.tokens, t.segments, t.q_tiles, t.padded_keys, t.short_rows, p->layout, &h);
   s->n_short_rows = (int32_t)t.short_rows;
+  s->layout = p->layout;
   s->plan_bytes = (int64_t)h.total_ints * 4;
   s->dense_mask_bytes = t.mask_bytes;
   s->attn_workspace_bytes = attn_workspace_layout(t.tokens, t.padded_keys, hkv, d, in_dtype).total;
@@ -169,8 +173,9 @@ static pv_status check_sizes(const pv_sizes* s, PlanHeader* h) {
     return PV_ERR_SHAPE;
   if (validate_heads(s->n_q_heads, s->n_kv_heads, s->head_dim, s->in_dtype) != PV_OK)
     return PV_ERR_SHAPE;
+  if (s->layout != PV_LAYOUT_APPENDED && s->layout != PV_LAYOUT_INTERLEAVED) return PV_ERR_SHAPE;
   plan_layout((int)s->batch, s->total_tokens, s->total_segments, s->n_q_tiles, s->padded_keys,
-              s->n_short_rows, h);
+              s->n_short_rows, s->layout, h);
   if (s->plan_bytes != (int64_t)h->total_ints * 4) return PV_ERR_SHAPE;
   return PV_OK;
 }
@@ -229,7 +234,7 @@ pv_status pv_build_mask(const pv_problem* problem, const pv_sizes* sizes, void* 
   if (sizes->batch != problem->batch || sizes->total_tokens != t.tokens ||
       sizes->total_segments != t.segments || sizes->n_q_tiles != t.q_tiles ||
       sizes->padded_keys != t.padded_keys || sizes->dense_mask_bytes != t.mask_bytes ||
-      sizes->n_short_rows != t.short_rows)
+      sizes->n_short_rows != t.short_rows || sizes->layout != problem->layout)
     return PV_ERR_SHAPE;
   if (!plan_dev) return PV_ERR_NULL;
   if (plan_bytes < sizes->plan_bytes) return PV_ERR_WORKSPACE;

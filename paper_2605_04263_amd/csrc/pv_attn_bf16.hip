@@ -54,8 +54,9 @@ __device__ void short_row(const int32_t* __restrict__ plan, const PlanHeader& h,
       *hi_out = xh * tc + xl * ts2;
     } else { *lo_out = xl; *hi_out = xh; }
   };
+  const int64_t g_row = caller_row(plan, h, g);        // this row in q / out / lse
   float ql, qh;
-  load_pair(a.q + ((int64_t)g * a.hq + head) * D, g, &ql, &qh);
+  load_pair(a.q + (g_row * a.hq + head) * D, g, &ql, &qh);
   // Visible keys: [0, a_end) then [max(b_start, a_end), i]; at most PV_SHORT_ROW_KEYS of them.
   // All loads are issued before any of them is used (fixed trip count, predicated).
   const int n_a = min(a_end, (int)PV_SHORT_ROW_KEYS);
@@ -66,8 +67,9 @@ __device__ void short_row(const int32_t* __restrict__ plan, const PlanHeader& h,
   for (int e = 0; e < PV_SHORT_ROW_KEYS; ++e) {
     const int key = e < n_a ? e : b0 + (e - n_a);
     const int tok = base + (e < n ? key : i);           // clamp to a valid row when predicated off
-    load_pair(k + ((int64_t)tok * hkv + kvh) * D, tok, &kl[e], &kh[e]);
-    const uint16_t* vr = v + ((int64_t)tok * hkv + kvh) * D;
+    const int64_t tok_row = caller_row(plan, h, tok);
+    load_pair(k + (tok_row * hkv + kvh) * D, tok, &kl[e], &kh[e]);
+    const uint16_t* vr = v + (tok_row * hkv + kvh) * D;
     vl[e] = __uint_as_float((unsigned)vr[c] << 16);
     vh[e] = __uint_as_float((unsigned)vr[c + HALF] << 16);
   }
@@ -90,7 +92,7 @@ __device__ void short_row(const int32_t* __restrict__ plan, const PlanHeader& h,
     oh = fmaf(p, vh[e], oh);
   }
   if (on) {
-    const int64_t row = ((int64_t)g * a.hq + head) * D;
+    const int64_t row = (g_row * a.hq + head) * D;
     if (a.out_f32) {
       float* op = reinterpret_cast<float*>(a.out) + row;
       op[c] = ol / l; op[c + HALF] = oh / l;
@@ -99,7 +101,7 @@ __device__ void short_row(const int32_t* __restrict__ plan, const PlanHeader& h,
       op[c] = (uint16_t)(pack_bf16(ol / l, 0.0f) & 0xffffu);
       op[c + HALF] = (uint16_t)(pack_bf16(oh / l, 0.0f) & 0xffffu);
     }
-    if (a.lse && lane == 0) a.lse[(int64_t)head * h.total_tokens + g] = m + logf(l);
+    if (a.lse && lane == 0) a.lse[(int64_t)head * h.total_tokens + g_row] = m + logf(l);
   }
 }
 
@@ -168,7 +170,8 @@ __global__ __launch_bounds__(256) void k_prep_kv(const int32_t* __restrict__ pla
       const int ch = item % (D / 8), hl = (item / (D / 8)) % nh, key = item / ((D / 8) * nh);
       uint4 w = make_uint4(0, 0, 0, 0);
       if (key0 + key < n_b)
-        w = *reinterpret_cast<const uint4*>(v + ((int64_t)(tok_base + key0 + key) * hkv + h0 + hl) * D + ch * 8);
+        w = *reinterpret_cast<const uint4*>(
+            v + (caller_row(plan, h, tok_base + key0 + key) * hkv + h0 + hl) * D + ch * 8);
       v_s[hl][key][ch] = w;
     }
     // K: item = (key, head, group of 8 rotation pairs); consecutive threads read consecutive
@@ -177,7 +180,7 @@ __global__ __launch_bounds__(256) void k_prep_kv(const int32_t* __restrict__ pla
       const int c0 = (item % (HALF / 8)) * 8, hl = (item / (HALF / 8)) % nh, key = item / ((HALF / 8) * nh);
       uint4 lo4 = make_uint4(0, 0, 0, 0), hi4 = make_uint4(0, 0, 0, 0);
       if (key0 + key < n_b) {
-        const uint16_t* src = k + ((int64_t)(tok_base + key0 + key) * hkv + h0 + hl) * D;
+        const uint16_t* src = k + (caller_row(plan, h, tok_base + key0 + key) * hkv + h0 + hl) * D;
         lo4 = *reinterpret_cast<const uint4*>(src + c0);
         hi4 = *reinterpret_cast<const uint4*>(src + c0 + HALF);
         if (rope) {
@@ -436,7 +439,7 @@ __global__ __launch_bounds__(G * 64, 2) __attribute__((amdgpu_waves_per_eu(2))) 
       const int Pg = (R << 4) + (pos ^ (R & 15));     // global chunk that lands at LDS chunk P
       const int row = Pg / CPR, ch = Pg % CPR;
       const int hl = row >> 5, tok = min(row & 31, rows_m1);
-      const uint16_t* src = q + ((tok0 + tok) * hq + kvh * G + hl) * D + (ch << 3);
+      const uint16_t* src = q + (caller_row(plan, h, tok0 + tok) * hq + kvh * G + hl) * D + (ch << 3);
       __builtin_amdgcn_global_load_lds(
           (const __attribute__((address_space(1))) void*)src,
           (__attribute__((address_space(3))) void*)(uintptr_t)(q_area + c * 1024), 16, 0, 0);
@@ -787,7 +790,8 @@ __global__ __launch_bounds__(G * 64, 2) __attribute__((amdgpu_waves_per_eu(2))) 
           const int row = it * (64 / LPR) + lane / LPR, c = lane % LPR;
           const float4 w = *reinterpret_cast<const float4*>(tr + row * RS + c * 16);
           if (stored(row))
-            *reinterpret_cast<float4*>(op + ((tok0 + row) * hq + head) * D + half * (D / 2) + c * 4) = w;
+            *reinterpret_cast<float4*>(op + (caller_row(plan, h, tok0 + row) * hq + head) * D +
+                                       half * (D / 2) + c * 4) = w;
         }
       }
     } else {
@@ -806,11 +810,13 @@ __global__ __launch_bounds__(G * 64, 2) __attribute__((amdgpu_waves_per_eu(2))) 
       for (int it = 0; it < 32 * LPR / 64; ++it) {
         const int row = it * (64 / LPR) + lane / LPR, c = lane % LPR;
         const uint4 w = *reinterpret_cast<const uint4*>(tr + row * RS + c * 16);
-        if (stored(row)) *reinterpret_cast<uint4*>(op + ((tok0 + row) * hq + head) * D + c * 8) = w;
+        if (stored(row))
+          *reinterpret_cast<uint4*>(op + (caller_row(plan, h, tok0 + row) * hq + head) * D + c * 8) = w;
       }
     }
     if (lse && hh == 0 && valid && a_end + i_loc - b_start + 1 > PV_SHORT_ROW_KEYS)
-      lse[(int64_t)head * h.total_tokens + g] = (log2f(l_tot) - nmref) * 0.6931471805599453f;
+      lse[(int64_t)head * h.total_tokens + caller_row(plan, h, g)] =
+          (log2f(l_tot) - nmref) * 0.6931471805599453f;
   }
 }
 

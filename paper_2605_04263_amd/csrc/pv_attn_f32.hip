@@ -17,15 +17,18 @@ __global__ __launch_bounds__(256) void k_rope_table(const int32_t* plan, PlanHea
   cs[idx] = make_float2((float)cn, (float)sn);
 }
 
-__global__ __launch_bounds__(256) void k_rotate_k_f32(const float* k, const float2* cs, int hkv,
-                                                      int d, int64_t total, float* k_rot, bool rope) {
+// k_rot is indexed by virtual row (the appended order); k by the caller's row.
+__global__ __launch_bounds__(256) void k_rotate_k_f32(const int32_t* plan, PlanHeader h, const float* k,
+                                                      const float2* cs, int hkv, int d, int64_t total,
+                                                      float* k_rot, bool rope) {
   const int half = d / 2;
   const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;   // (g, head, c)
   if (idx >= total * hkv * half) return;
   const int c = (int)(idx % half);
   const int64_t gh = idx / half;
   const int64_t g = gh / hkv;
-  const float lo = k[gh * d + c], hi = k[gh * d + c + half];
+  const int64_t src = (caller_row(plan, h, g) * hkv + gh % hkv) * d;
+  const float lo = k[src + c], hi = k[src + c + half];
   float2 t = rope ? cs[g * half + c] : make_float2(1.0f, 0.0f);
   k_rot[gh * d + c] = lo * t.x - hi * t.y;
   k_rot[gh * d + c + half] = hi * t.x + lo * t.y;
@@ -50,7 +53,8 @@ __global__ __launch_bounds__(64) void k_attn_f32(const int32_t* plan, PlanHeader
   const int a_end = plan[h.off_aend + g], b_start = plan[h.off_bstart + g];
 
   float qr[D];
-  const float* qp = q + idx * D;
+  const int64_t g_row = caller_row(plan, h, g);        // this row in q / v / out / lse
+  const float* qp = q + (g_row * hq + head) * D;
 #pragma unroll
   for (int c = 0; c < HALF; ++c) {
     const float lo = qp[c], hi = qp[c + HALF];
@@ -76,17 +80,17 @@ __global__ __launch_bounds__(64) void k_attn_f32(const int32_t* plan, PlanHeader
       const float alpha = expf(m - m_new);      // exp(-inf) = 0 on the first key
       const float p = expf(s - m_new);
       l = l * alpha + p;
-      const float* vp = v + ((int64_t)(base + j) * hkv + kvh) * D;
+      const float* vp = v + (caller_row(plan, h, base + j) * hkv + kvh) * D;
 #pragma unroll
       for (int c = 0; c < D; ++c) acc[c] = fmaf(p, vp[c], acc[c] * alpha);
       m = m_new;
     }
   }
   const float inv = 1.0f / l;
-  float* op = out + idx * D;
+  float* op = out + (g_row * hq + head) * D;
 #pragma unroll
   for (int c = 0; c < D; ++c) op[c] = acc[c] * inv;
-  if (lse) lse[(int64_t)head * h.total_tokens + g] = m + logf(l);
+  if (lse) lse[(int64_t)head * h.total_tokens + g_row] = m + logf(l);
 }
 
 hipError_t launch_attn_f32(const int32_t* plan_dev, const PlanHeader& h, const float* q,
@@ -108,7 +112,7 @@ hipError_t launch_attn_f32(const int32_t* plan_dev, const PlanHeader& h, const f
   {
     const int64_t n = (int64_t)h.total_tokens * hkv * half;
     if (!grid_1d((n + 255) / 256, 256, &grid)) return hipErrorInvalidConfiguration;
-    k_rotate_k_f32<<<grid, dim3(256), 0, s>>>(k, cs, hkv, d, h.total_tokens, k_rot, rope);
+    k_rotate_k_f32<<<grid, dim3(256), 0, s>>>(plan_dev, h, k, cs, hkv, d, h.total_tokens, k_rot, rope);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
   }

@@ -34,7 +34,9 @@ struct PlanHeader {
   int32_t off_tiles, off_work;                           // [n_q_tiles][8] each
   int32_t total_ints;
   int32_t n_short_rows;
-  int32_t pad[4];
+  int32_t layout;                                        // PV_LAYOUT_*
+  int32_t off_map;                                       // [total_tokens], interleaved layout only
+  int32_t pad[2];
 };
 static_assert(sizeof(PlanHeader) == 32 * 4, "PlanHeader must be 32 ints");
 
@@ -44,6 +46,14 @@ inline bool grid_1d(int64_t blocks, int threads, dim3* grid) {
   if (blocks < 1 || blocks * threads > 0xffffffffll) return false;
   *grid = dim3((unsigned)blocks);
   return true;
+}
+
+// The kernels work on "virtual" rows in the appended order [prompt | draft | segments] of every
+// request.  For the interleaved layout the same tokens sit elsewhere in the caller's tensors; the
+// plan then holds, per virtual row, the caller's row.  Everything the plan stores per token (position,
+// row descriptor) and the K/V workspaces are indexed by virtual row.
+__device__ inline int64_t caller_row(const int32_t* plan, const PlanHeader& h, int64_t g) {
+  return h.layout == PV_LAYOUT_INTERLEAVED ? (int64_t)plan[h.off_map + g] : g;
 }
 
 // One query tile of the work list (8 ints).
@@ -93,7 +103,7 @@ hipError_t launch_attn_bf16(const int32_t* plan_dev, const PlanHeader& h, const 
 
 // Host-side layout of the plan; shared by pv_query_sizes and pv_build_mask.
 void plan_layout(int batch, int64_t total_tokens, int64_t total_segments, int64_t n_q_tiles,
-                 int64_t padded_keys, int64_t n_short_rows, PlanHeader* h);
+                 int64_t padded_keys, int64_t n_short_rows, int layout, PlanHeader* h);
 
 }  // namespace pv
 #endif

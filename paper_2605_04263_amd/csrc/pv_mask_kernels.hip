@@ -62,6 +62,27 @@ __device__ inline void row_desc(const Req& r, int i, int* pos, int* a_end, int* 
   }
 }
 
+// Interleaved packing ("Parallel partial verify"): where local token i of the appended order
+// [prompt | draft | segments] sits when every segment follows the draft tokens it judges.  A draft
+// token is pushed back by the segments whose boundary does not exceed it; segment k comes after
+// its p_k draft tokens and the k segments before it.
+__device__ inline int interleaved_row(const Req& r, int i) {
+  const int c = r.P + r.T;
+  if (i < r.P) return i;
+  if (i < c) {
+    const int t = i - r.P;
+    int lo = 0, hi = r.K;          // number of boundaries <= t
+    while (lo < hi) {
+      const int mid = (lo + hi) >> 1;
+      if (r.bounds[mid] <= t) lo = mid + 1; else hi = mid;
+    }
+    return i + lo * r.S;
+  }
+  const int k = (i - c) / r.S;
+  const int a = (i - c) - k * r.S;
+  return r.P + r.bounds[k] + k * r.S + a;
+}
+
 // Largest b with start[b] <= x, for a non-decreasing start[0..n] with start[0] = 0 <= x < start[n].
 __device__ inline int find_owner(const int32_t* start, int n, int x) {
   int lo = 0, hi = n;            // invariant: start[lo] <= x < start[hi]
@@ -85,13 +106,17 @@ __device__ inline void plan_token(int32_t* plan, const int32_t* img, const PlanH
     plan[h.off_pos + g] = pos;
     plan[h.off_aend + g] = ae;
     plan[h.off_bstart + g] = bs;
+    if (h.layout == PV_LAYOUT_INTERLEAVED)
+      plan[h.off_map + g] = img[h.off_tok_start + b] + interleaved_row(r, g - img[h.off_tok_start + b]);
   }
   if (g < h.total_segments) {
     const int b = find_owner(img + h.off_seg_start, h.batch, g);
     const Req r = load_req(img, h, b);
     const int k = g - img[h.off_seg_start + b];
-    // the verdict of segment k is read at its last token
-    plan[h.off_judge + g] = img[h.off_tok_start + b] + r.P + r.T + (k + 1) * r.S - 1;
+    // the verdict of segment k is read at its last token (a row of the caller's tensors)
+    const int last = r.P + r.T + (k + 1) * r.S - 1;
+    plan[h.off_judge + g] = img[h.off_tok_start + b] +
+                            (h.layout == PV_LAYOUT_INTERLEAVED ? interleaved_row(r, last) : last);
   }
 }
 
@@ -198,9 +223,10 @@ __global__ __launch_bounds__(256) void k_dense_mask(const int32_t* plan, PlanHea
   const int i = g - base;
   const int ae = plan[h.off_aend + g], bs = plan[h.off_bstart + g];
   const int64_t* mask_start = reinterpret_cast<const int64_t*>(plan + h.off_mask_start);
-  uint8_t* row = mask + mask_start[b] + (int64_t)i * n;
+  // rows and columns of the mask follow the caller's row order
+  uint8_t* row = mask + mask_start[b] + (caller_row(plan, h, g) - base) * n;
   for (int j = threadIdx.x; j < n; j += blockDim.x)
-    row[j] = (j < ae) || (j >= bs && j <= i) ? 1 : 0;
+    row[caller_row(plan, h, base + j) - base] = (j < ae) || (j >= bs && j <= i) ? 1 : 0;
 }
 
 hipError_t launch_plan_kernels(int32_t* plan_dev, const PlanHeader& h, const int32_t* host_ints,
@@ -242,9 +268,10 @@ __global__ __launch_bounds__(256) void k_export(const int32_t* plan, PlanHeader 
                                                 int32_t* aend, int32_t* bstart, int32_t* judge) {
   const int g = blockIdx.x * blockDim.x + threadIdx.x;
   if (g < h.total_tokens) {
-    if (pos) pos[g] = plan[h.off_pos + g];
-    if (aend) aend[g] = plan[h.off_aend + g];
-    if (bstart) bstart[g] = plan[h.off_bstart + g];
+    const int64_t row = caller_row(plan, h, g);
+    if (pos) pos[row] = plan[h.off_pos + g];
+    if (aend) aend[row] = plan[h.off_aend + g];
+    if (bstart) bstart[row] = plan[h.off_bstart + g];
   }
   if (judge && g < h.total_segments) judge[g] = plan[h.off_judge + g];
 }

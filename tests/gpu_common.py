@@ -15,7 +15,7 @@ def make_verifier(pv, w, dense_mask=False):
     pr = w.problem
     return pv.Verifier(pr.prompt_len, pr.draft_len, pr.num_segments, pr.segment_len,
                        pr.flat_boundaries(), w.n_q_heads, w.n_kv_heads, w.head_dim, w.dtype,
-                       dense_mask=dense_mask)
+                       dense_mask=dense_mask, layout=pr.layout)
 
 
 def run_gpu_attention(pv, w, out_dtype=None, lse=False, ver=None):
@@ -36,14 +36,15 @@ def oracle_attention(w, rows_per_request=None, return_lse=False):
     return orc.masked_attention(pr.prompt_len, pr.draft_len, pr.num_segments, pr.segment_len,
                                 pr.boundaries, w.q.double().numpy(), w.k.double().numpy(),
                                 w.v.double().numpy(), rope_theta=w.rope_theta,
-                                rows_per_request=rows_per_request, return_lse=return_lse)
+                                rows_per_request=rows_per_request, return_lse=return_lse, layout=pr.layout)
 
 
 def oracle_dense_mask_flat(pr):
     parts = []
+    mask_fn = orc.dense_mask_interleaved if pr.layout == orc.LAYOUT_INTERLEAVED else orc.dense_mask
     for b in range(pr.batch):
-        parts.append(orc.dense_mask(pr.prompt_len[b], pr.draft_len[b], pr.segment_len[b],
-                                    pr.boundaries[b]).reshape(-1))
+        parts.append(mask_fn(pr.prompt_len[b], pr.draft_len[b], pr.segment_len[b],
+                             pr.boundaries[b]).reshape(-1))
     return np.concatenate(parts)
 
 
@@ -52,8 +53,12 @@ def oracle_plan_arrays(pr):
     cu = pr.token_offsets()
     for b in range(pr.batch):
         P, T, K, S = pr.prompt_len[b], pr.draft_len[b], pr.num_segments[b], pr.segment_len[b]
-        pos.append(orc.positions(P, T, S, pr.boundaries[b]))
-        jr.append(orc.judge_rows(P, T, S, K) + cu[b])
+        if pr.layout == orc.LAYOUT_INTERLEAVED:
+            pos.append(orc.positions_interleaved(P, T, S, pr.boundaries[b]))
+            jr.append(orc.judge_rows_interleaved(P, T, S, pr.boundaries[b]) + cu[b])
+        else:
+            pos.append(orc.positions(P, T, S, pr.boundaries[b]))
+            jr.append(orc.judge_rows(P, T, S, K) + cu[b])
     return np.concatenate(pos), np.concatenate(jr) if jr else np.zeros(0, np.int64)
 
 

@@ -171,3 +171,22 @@ def test_policy_calls_reject_bad_arguments_before_touching_the_gpu():
     assert jl(hs=0) == pv.PV_ERR_SHAPE
     assert jl(w=fake + 2) == pv.PV_ERR_ALIGN
     assert jl(plan=None) == pv.PV_ERR_NULL
+
+
+def test_layout_is_validated_and_sized():
+    args = ([4], [16], [2], [3], [5, 9])
+    st, s0 = q(pv.make_problem(*args), 8, 2, 128)
+    inter = pv.make_problem(*args, layout=pv.PV_LAYOUT_INTERLEAVED)
+    st1, s1 = q(inter, 8, 2, 128)
+    assert st == st1 == pv.PV_OK
+    assert s1.layout == pv.PV_LAYOUT_INTERLEAVED and s0.layout == pv.PV_LAYOUT_APPENDED
+    assert s1.plan_bytes >= s0.plan_bytes + 4 * s0.total_tokens        # the row map
+    assert (s1.total_tokens, s1.n_q_tiles, s1.padded_keys) == (s0.total_tokens, s0.n_q_tiles, s0.padded_keys)
+    bad = pv.make_problem(*args, layout=2)
+    assert q(bad, 8, 2, 128)[0] == pv.PV_ERR_SHAPE
+    fake = 0x1000
+    # sizes of one layout with a problem of the other: refused before any launch
+    assert pv.lib.pv_build_mask(C.byref(inter.struct), C.byref(s0), fake, s1.plan_bytes, None, 0, None) == pv.PV_ERR_SHAPE
+    tampered = pv.PvSizes.from_buffer_copy(s0)
+    tampered.layout = pv.PV_LAYOUT_INTERLEAVED                         # plan_bytes no longer matches
+    assert pv.lib.pv_first_reject(C.byref(tampered), fake, fake, 0.0, 0, fake, None) == pv.PV_ERR_SHAPE
