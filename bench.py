@@ -75,11 +75,12 @@ def cpu_baseline(w, eff_flops: float) -> dict:
         sample = f"{sum(len(r) for r in rows)} seeded random query rows (all heads) of {pr.total_tokens}"
         pairs = 0
         for b in range(pr.batch):
-            M = orc.dense_mask(pr.prompt_len[b], pr.draft_len[b], pr.segment_len[b], pr.boundaries[b], rows[b])
+            mask_fn = orc.dense_mask_interleaved if pr.layout == orc.LAYOUT_INTERLEAVED else orc.dense_mask
+            M = mask_fn(pr.prompt_len[b], pr.draft_len[b], pr.segment_len[b], pr.boundaries[b], rows[b])
             pairs += int(M.sum(dtype=np.int64))
     t0 = time.perf_counter()
     orc.masked_attention(pr.prompt_len, pr.draft_len, pr.num_segments, pr.segment_len, pr.boundaries,
-                         q, k, v, rope_theta=w.rope_theta, rows_per_request=rows)
+                         q, k, v, rope_theta=w.rope_theta, rows_per_request=rows, layout=pr.layout)
     orc.first_reject(w.logits.numpy(), pr.num_segments, pr.boundaries, orc.margin_threshold(w.tau), 0)
     dt = time.perf_counter() - t0
     flops = 4.0 * w.head_dim * w.n_q_heads * pairs
@@ -94,6 +95,8 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="8b")
+    ap.add_argument("--layout", default="appended", choices=["appended", "interleaved"],
+                    help="row order of the packed tensors: segments after the draft, or each after its chunk")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 256 MiB device copy (reference for HBM byte counters)")
@@ -114,10 +117,14 @@ def main() -> int:
     dev = torch.device("cuda:0")
     w = wl.make(args.workload)
     pr = w.problem
+    if args.layout == "interleaved":
+        import dataclasses
+        pr = dataclasses.replace(pr, layout=1)
+        w = wl.Workload(**{**w.__dict__, "problem": pr})
     if w.dtype != torch.bfloat16:
         w = wl.make_custom(pr, w.n_q_heads, w.n_kv_heads, w.head_dim, torch.bfloat16, w.rope_theta, w.seed)
     ver = pv.Verifier(pr.prompt_len, pr.draft_len, pr.num_segments, pr.segment_len, pr.flat_boundaries(),
-                      w.n_q_heads, w.n_kv_heads, w.head_dim, torch.bfloat16)
+                      w.n_q_heads, w.n_kv_heads, w.head_dim, torch.bfloat16, layout=pr.layout)
     q, k, v, logits = w.q.to(dev), w.k.to(dev), w.v.to(dev), w.logits.to(dev)
     out = torch.empty_like(q)
     thr = pv.margin_from_tau(w.tau)
@@ -194,7 +201,7 @@ def main() -> int:
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": w.name, "batch": pr.batch, "n_q_heads": w.n_q_heads, "n_kv_heads": w.n_kv_heads,
+        "config": {"workload": w.name, "layout": args.layout, "batch": pr.batch, "n_q_heads": w.n_q_heads, "n_kv_heads": w.n_kv_heads,
                    "head_dim": w.head_dim, "total_tokens": pr.total_tokens, "total_segments": pr.total_segments,
                    "rope_theta": w.rope_theta, "unmasked_pairs": pairs, "effective_flops": eff_flops,
                    "layers": 1},
