@@ -134,15 +134,23 @@ __device__ inline QTile plan_tile(const int32_t* plan, const PlanHeader& h, int 
   int min_prefix = 0x7fffffff;   // min over rows of the length of the fully visible key prefix
   int max_low = 0;               // max over rows of the end of the low range
   int min_b = 0x7fffffff, max_i = -1;
-  for (int rr = 0; rr < rows; ++rr) {
-    const int i = t0 + rr;
-    int pos, ae, bs;
-    row_desc(r, i, &pos, &ae, &bs);
-    const bool causal = (i < r.P + r.T);
-    const int low_end = causal ? i + 1 : ae;
-    min_prefix = min(min_prefix, low_end);
-    max_low = max(max_low, low_end);
-    if (!causal) { min_b = min(min_b, bs); max_i = max(max_i, i); }
+  // The rows of a tile are consecutive, causal rows first.  Their low range ends at i + 1, which
+  // grows with i; a segment row's ends at P + p_k and its second range starts at the segment's
+  // first row, both non-decreasing in k because the boundaries are sorted.  The extremes over the
+  // tile therefore sit at the first and last row of each kind.
+  const int c = r.P + r.T, last = t0 + rows - 1;
+  if (t0 < c) {
+    min_prefix = t0 + 1;
+    max_low = min(last, c - 1) + 1;
+  }
+  if (last >= c) {
+    int pos, ae0, bs0, ae1, bs1;
+    row_desc(r, max(t0, c), &pos, &ae0, &bs0);
+    row_desc(r, last, &pos, &ae1, &bs1);
+    min_prefix = min(min_prefix, ae0);
+    max_low = max(max_low, ae1);
+    min_b = bs0;
+    max_i = last;
   }
   QTile q;
   q.tok_base = plan[h.off_tok_start + b];
@@ -284,33 +292,46 @@ hipError_t launch_plan_export(const int32_t* plan_dev, const PlanHeader& h, int3
 }
 
 // ---------------------------------------------------------------- readout
-// One thread per request.  A verdict is Correct iff the fp64 margin l_C - l_I is non-negative
-// (ties count as Correct) and reaches the threshold.
-__global__ __launch_bounds__(64) void k_first_reject(const int32_t* plan, PlanHeader h,
-                                                     const float* logits, double thr, int mode,
-                                                     int32_t* out) {
-  const int b = blockIdx.x * blockDim.x + threadIdx.x;
-  if (b >= h.batch) return;
+// One wave per request: lane l takes segments l, l + 64, ..., so the logits of a request arrive
+// in one round of loads; the three per-request quantities are then a min, a max and a sum over
+// the wave.  A verdict is Correct iff the fp64 margin l_C - l_I is non-negative (ties count as
+// Correct) and reaches the threshold.
+__global__ __launch_bounds__(256) void k_first_reject(const int32_t* plan, PlanHeader h,
+                                                      const float* logits, double thr, int mode,
+                                                      int32_t* out) {
+  const int b = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+  if (b >= h.batch) return;                     // whole waves leave together
   const int s0 = plan[h.off_seg_start + b];
   const int K = plan[h.off_nseg + b];
   const int32_t* bounds = plan + h.off_bounds + s0;
   int first = K, last_ok = -1, bad = 0;
-  for (int k = 0; k < K; ++k) {
-    const double d = (double)logits[2 * (s0 + k)] - (double)logits[2 * (s0 + k) + 1];
+  for (int k = lane; k < K; k += 64) {
+    const float2 lg = reinterpret_cast<const float2*>(logits)[s0 + k];
+    const double d = (double)lg.x - (double)lg.y;
     const bool ok = (d >= 0.0) && (d >= thr);
-    if (ok) last_ok = k;
-    else { bad++; if (first == K) first = k; }
+    if (ok) last_ok = k;                        // k grows: the last one written is the largest
+    else { bad++; first = min(first, k); }
   }
-  const int k_star = (mode == 0) ? first - 1 : last_ok;
-  out[4 * b + 0] = first;
-  out[4 * b + 1] = k_star;
-  out[4 * b + 2] = k_star >= 0 ? bounds[k_star] : 0;
-  out[4 * b + 3] = bad;
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) {
+    first = min(first, __shfl_xor(first, off));
+    last_ok = max(last_ok, __shfl_xor(last_ok, off));
+    bad += __shfl_xor(bad, off);
+  }
+  if (lane == 0) {
+    const int k_star = (mode == 0) ? first - 1 : last_ok;
+    int4 o;
+    o.x = first;
+    o.y = k_star;
+    o.z = k_star >= 0 ? bounds[k_star] : 0;
+    o.w = bad;
+    reinterpret_cast<int4*>(out)[b] = o;
+  }
 }
 
 hipError_t launch_first_reject(const int32_t* plan_dev, const PlanHeader& h, const float* logits,
                                double thr, int mode, int32_t* out, hipStream_t s) {
-  k_first_reject<<<dim3((h.batch + 63) / 64), dim3(64), 0, s>>>(plan_dev, h, logits, thr, mode, out);
+  k_first_reject<<<dim3((h.batch + 3) / 4), dim3(256), 0, s>>>(plan_dev, h, logits, thr, mode, out);
   return hipGetLastError();
 }
 
