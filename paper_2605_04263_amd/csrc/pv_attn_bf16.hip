@@ -29,22 +29,27 @@ struct ShortRowArgs {          // what the fp32 evaluation of the short rows nee
 };
 
 // Rows with at most PV_SHORT_ROW_KEYS visible keys, in plain fp32 (the main kernel does not store
-// them).  One wave per (row, query head); lane c owns the rotation pair (c, c + D/2).
+// them).  One workgroup per (row, kv head): all threads first rotate the row's visible keys into
+// LDS (one rotary angle per thread and pass instead of one per key and lane), then wave w
+// evaluates query head kvh*G + w (+4, ...), lane c owning the rotation pair (c, c + D/2).
 template <int D>
-__device__ void short_row(const int32_t* __restrict__ plan, const PlanHeader& h,
-                          const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
-                          const RopeFreq& f, int hkv, bool rope, const ShortRowArgs& a,
-                          int g, int head, int lane) {
+__device__ void short_row_block(const int32_t* __restrict__ plan, const PlanHeader& h,
+                                const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
+                                const RopeFreq& f, int hkv, bool rope, const ShortRowArgs& a,
+                                int g, int kvh, float (*ks)[D], float (*vs)[D]) {
   constexpr int HALF = D / 2;
-  const int kvh = head / (a.hq / hkv);
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int G = a.hq / hkv;
   const int32_t* ts = plan + h.off_tok_start;
   int lo = 0, hi = h.batch;
   while (hi - lo > 1) { const int mid = (lo + hi) >> 1; if (ts[mid] <= g) lo = mid; else hi = mid; }
   const int base = ts[lo], i = g - base;
   const int a_end = plan[h.off_aend + g], b_start = plan[h.off_bstart + g];
-  const bool on = lane < HALF;
-  const int c = on ? lane : 0;
-  auto load_pair = [&](const uint16_t* row, int tok, float* lo_out, float* hi_out) {
+  // Visible keys: [0, a_end) then [max(b_start, a_end), i]; at most PV_SHORT_ROW_KEYS of them.
+  const int n_a = min(a_end, (int)PV_SHORT_ROW_KEYS);
+  const int b0 = max(b_start, a_end);
+  const int n = min(n_a + max(i - b0 + 1, 0), (int)PV_SHORT_ROW_KEYS);
+  auto rotate = [&](const uint16_t* row, int tok, int c, float* lo_out, float* hi_out) {
     const float xl = __uint_as_float((unsigned)row[c] << 16), xh = __uint_as_float((unsigned)row[c + HALF] << 16);
     if (rope) {
       double sn, cn;
@@ -54,54 +59,56 @@ __device__ void short_row(const int32_t* __restrict__ plan, const PlanHeader& h,
       *hi_out = xh * tc + xl * ts2;
     } else { *lo_out = xl; *hi_out = xh; }
   };
-  const int64_t g_row = caller_row(plan, h, g);        // this row in q / out / lse
-  float ql, qh;
-  load_pair(a.q + (g_row * a.hq + head) * D, g, &ql, &qh);
-  // Visible keys: [0, a_end) then [max(b_start, a_end), i]; at most PV_SHORT_ROW_KEYS of them.
-  // All loads are issued before any of them is used (fixed trip count, predicated).
-  const int n_a = min(a_end, (int)PV_SHORT_ROW_KEYS);
-  const int b0 = max(b_start, a_end);
-  const int n = min(n_a + max(i - b0 + 1, 0), (int)PV_SHORT_ROW_KEYS);
-  float kl[PV_SHORT_ROW_KEYS], kh[PV_SHORT_ROW_KEYS], vl[PV_SHORT_ROW_KEYS], vh[PV_SHORT_ROW_KEYS];
-#pragma unroll
-  for (int e = 0; e < PV_SHORT_ROW_KEYS; ++e) {
+  for (int item = tid; item < n * HALF; item += 256) {
+    const int e = item / HALF, c = item % HALF;
     const int key = e < n_a ? e : b0 + (e - n_a);
-    const int tok = base + (e < n ? key : i);           // clamp to a valid row when predicated off
+    const int tok = base + key;
     const int64_t tok_row = caller_row(plan, h, tok);
-    load_pair(k + (tok_row * hkv + kvh) * D, tok, &kl[e], &kh[e]);
+    rotate(k + (tok_row * hkv + kvh) * D, tok, c, &ks[e][c], &ks[e][c + HALF]);
     const uint16_t* vr = v + (tok_row * hkv + kvh) * D;
-    vl[e] = __uint_as_float((unsigned)vr[c] << 16);
-    vh[e] = __uint_as_float((unsigned)vr[c + HALF] << 16);
+    vs[e][c] = __uint_as_float((unsigned)vr[c] << 16);
+    vs[e][c + HALF] = __uint_as_float((unsigned)vr[c + HALF] << 16);
   }
-  float sc[PV_SHORT_ROW_KEYS];
-  float m = -INFINITY;
+  __syncthreads();
+  const bool on = lane < HALF;
+  const int c = on ? lane : 0;
+  const int64_t g_row = caller_row(plan, h, g);        // this row in q / out / lse
+  for (int hl = wave; hl < G; hl += 4) {
+    const int head = kvh * G + hl;
+    float ql, qh;
+    rotate(a.q + (g_row * a.hq + head) * D, g, c, &ql, &qh);
+    float sc[PV_SHORT_ROW_KEYS];
+    float m = -INFINITY;
 #pragma unroll
-  for (int e = 0; e < PV_SHORT_ROW_KEYS; ++e) {
-    float part = on ? ql * kl[e] + qh * kh[e] : 0.0f;
+    for (int e = 0; e < PV_SHORT_ROW_KEYS; ++e) {
+      float part = (on && e < n) ? ql * ks[e][c] + qh * ks[e][c + HALF] : 0.0f;
 #pragma unroll
-    for (int off = 32; off > 0; off >>= 1) part += __shfl_xor(part, off);
-    sc[e] = e < n ? part * a.scale : -INFINITY;
-    m = fmaxf(m, sc[e]);
-  }
-  float l = 0.0f, ol = 0.0f, oh = 0.0f;
-#pragma unroll
-  for (int e = 0; e < PV_SHORT_ROW_KEYS; ++e) {
-    const float p = expf(sc[e] - m);                    // exp(-inf) = 0 for the unused slots
-    l += p;
-    ol = fmaf(p, vl[e], ol);
-    oh = fmaf(p, vh[e], oh);
-  }
-  if (on) {
-    const int64_t row = (g_row * a.hq + head) * D;
-    if (a.out_f32) {
-      float* op = reinterpret_cast<float*>(a.out) + row;
-      op[c] = ol / l; op[c + HALF] = oh / l;
-    } else {
-      uint16_t* op = reinterpret_cast<uint16_t*>(a.out) + row;
-      op[c] = (uint16_t)(pack_bf16(ol / l, 0.0f) & 0xffffu);
-      op[c + HALF] = (uint16_t)(pack_bf16(oh / l, 0.0f) & 0xffffu);
+      for (int off = 32; off > 0; off >>= 1) part += __shfl_xor(part, off);
+      sc[e] = e < n ? part * a.scale : -INFINITY;
+      m = fmaxf(m, sc[e]);
     }
-    if (a.lse && lane == 0) a.lse[(int64_t)head * h.total_tokens + g_row] = m + logf(l);
+    float l = 0.0f, ol = 0.0f, oh = 0.0f;
+#pragma unroll
+    for (int e = 0; e < PV_SHORT_ROW_KEYS; ++e) {
+      const float p = expf(sc[e] - m);                  // exp(-inf) = 0 for the unused slots
+      l += p;
+      if (e < n) {
+        ol = fmaf(p, vs[e][c], ol);
+        oh = fmaf(p, vs[e][c + HALF], oh);
+      }
+    }
+    if (on) {
+      const int64_t row = (g_row * a.hq + head) * D;
+      if (a.out_f32) {
+        float* op = reinterpret_cast<float*>(a.out) + row;
+        op[c] = ol / l; op[c + HALF] = oh / l;
+      } else {
+        uint16_t* op = reinterpret_cast<uint16_t*>(a.out) + row;
+        op[c] = (uint16_t)(pack_bf16(ol / l, 0.0f) & 0xffffu);
+        op[c + HALF] = (uint16_t)(pack_bf16(oh / l, 0.0f) & 0xffffu);
+      }
+      if (a.lse && lane == 0) a.lse[(int64_t)head * h.total_tokens + g_row] = m + logf(l);
+    }
   }
 }
 
@@ -118,17 +125,20 @@ __global__ __launch_bounds__(256) void k_prep_kv(const int32_t* __restrict__ pla
   constexpr int HALF = D / 2;
   constexpr int KB = 16;                       // keys per block
   constexpr int HG = 2;                        // kv heads per block
+  // one LDS area, used either by a short-row block or by a key block
+  constexpr int CS_BYTES = KB * HALF * 8, VS_BYTES = HG * KB * (D / 8 + 1) * 16;
+  static_assert(2 * PV_SHORT_ROW_KEYS * D * 4 <= CS_BYTES + VS_BYTES, "short-row tiles must fit");
+  __shared__ uint4 lds[(CS_BYTES + VS_BYTES) / 16];
   const int n_short_blocks = h.n_short_rows * hkv;
   if ((int)blockIdx.x < n_short_blocks) {      // one (short row, kv head) each
     const int idx = (int)blockIdx.x;
     const int g = plan[h.off_short + idx / hkv], kvh = idx % hkv;
-    const int G = sr.hq / hkv;
-    for (int hl = threadIdx.x >> 6; hl < G; hl += 4)
-      short_row<D>(plan, h, k, v, f, hkv, rope, sr, g, kvh * G + hl, threadIdx.x & 63);
+    float (*ks)[D] = reinterpret_cast<float (*)[D]>(&lds[0]);
+    short_row_block<D>(plan, h, k, v, f, hkv, rope, sr, g, kvh, ks, ks + PV_SHORT_ROW_KEYS);
     return;
   }
-  __shared__ float2 cs_s[KB][HALF];            // cos/sin of the block's tokens
-  __shared__ uint4 v_s[HG][KB][D / 8 + 1];     // V rows of one pass, padded
+  float2 (*cs_s)[HALF] = reinterpret_cast<float2 (*)[HALF]>(&lds[0]);                       // cos/sin of the block's tokens
+  uint4 (*v_s)[KB][D / 8 + 1] = reinterpret_cast<uint4 (*)[KB][D / 8 + 1]>(&lds[CS_BYTES / 16]);   // V rows of one pass, padded
   const int n_hg = (hkv + HG - 1) / HG;        // head groups
   const int mb = (int)blockIdx.x - n_short_blocks;
   const int row0 = (mb / n_hg) * KB;           // first padded key row of this block
