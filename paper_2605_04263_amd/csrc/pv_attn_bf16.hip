@@ -157,6 +157,32 @@ __global__ __launch_bounds__(256) void k_prep_kv(const int32_t* __restrict__ pla
   const int key0 = row0 - kp[b];               // first local key of the block
   const int tid = threadIdx.x;
 
+  // The K and V rows of the block are requested first, so that their latency overlaps the rotary
+  // angles below.  V item = (key, head, 16-byte piece); K item = (key, head, group of 8 rotation
+  // pairs): consecutive threads read consecutive 16-byte pieces of a token's row.
+  constexpr int VIT = (HG * KB * (D / 8) + 255) / 256, KIT = (HG * KB * (HALF / 8) + 255) / 256;
+  uint4 v_reg[VIT], k_lo[KIT], k_hi[KIT];
+#pragma unroll
+  for (int it = 0; it < VIT; ++it) {
+    const int item = tid + it * 256;
+    const int ch = item % (D / 8), hl = (item / (D / 8)) % nh, key = item / ((D / 8) * nh);
+    v_reg[it] = make_uint4(0, 0, 0, 0);
+    if (item < nh * KB * (D / 8) && key0 + key < n_b)
+      v_reg[it] = *reinterpret_cast<const uint4*>(
+          v + (caller_row(plan, h, tok_base + key0 + key) * hkv + h0 + hl) * D + ch * 8);
+  }
+#pragma unroll
+  for (int it = 0; it < KIT; ++it) {
+    const int item = tid + it * 256;
+    const int c0 = (item % (HALF / 8)) * 8, hl = (item / (HALF / 8)) % nh, key = item / ((HALF / 8) * nh);
+    k_lo[it] = make_uint4(0, 0, 0, 0);
+    k_hi[it] = make_uint4(0, 0, 0, 0);
+    if (item < nh * KB * (HALF / 8) && key0 + key < n_b) {
+      const uint16_t* src = k + (caller_row(plan, h, tok_base + key0 + key) * hkv + h0 + hl) * D;
+      k_lo[it] = *reinterpret_cast<const uint4*>(src + c0);
+      k_hi[it] = *reinterpret_cast<const uint4*>(src + c0 + HALF);
+    }
+  }
   // cos/sin of the rotary angles: fp64 angle, fp32 result, also written to the table that the
   // main kernel rotates Q with
   if (rope) {
@@ -174,37 +200,30 @@ __global__ __launch_bounds__(256) void k_prep_kv(const int32_t* __restrict__ pla
     }
   }
   {
-    __syncthreads();                           // cs_s ready
-    // V rows into LDS with 16-byte loads
-    for (int item = tid; item < nh * KB * (D / 8); item += 256) {
-      const int ch = item % (D / 8), hl = (item / (D / 8)) % nh, key = item / ((D / 8) * nh);
-      uint4 w = make_uint4(0, 0, 0, 0);
-      if (key0 + key < n_b)
-        w = *reinterpret_cast<const uint4*>(
-            v + (caller_row(plan, h, tok_base + key0 + key) * hkv + h0 + hl) * D + ch * 8);
-      v_s[hl][key][ch] = w;
-    }
-    // K: item = (key, head, group of 8 rotation pairs); consecutive threads read consecutive
-    // 16-byte pieces of the token's K row
-    for (int item = tid; item < nh * KB * (HALF / 8); item += 256) {
-      const int c0 = (item % (HALF / 8)) * 8, hl = (item / (HALF / 8)) % nh, key = item / ((HALF / 8) * nh);
-      uint4 lo4 = make_uint4(0, 0, 0, 0), hi4 = make_uint4(0, 0, 0, 0);
-      if (key0 + key < n_b) {
-        const uint16_t* src = k + (caller_row(plan, h, tok_base + key0 + key) * hkv + h0 + hl) * D;
-        lo4 = *reinterpret_cast<const uint4*>(src + c0);
-        hi4 = *reinterpret_cast<const uint4*>(src + c0 + HALF);
-        if (rope) {
-          const float2* t = &cs_s[key][c0];
-          unsigned* pl = reinterpret_cast<unsigned*>(&lo4);
-          unsigned* ph = reinterpret_cast<unsigned*>(&hi4);
 #pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            const float2 t0 = t[2 * e], t1 = t[2 * e + 1];
-            const float l0 = bf16_lo(pl[e]), l1 = bf16_hi(pl[e]);
-            const float h0f = bf16_lo(ph[e]), h1f = bf16_hi(ph[e]);
-            pl[e] = pack_bf16(l0 * t0.x - h0f * t0.y, l1 * t1.x - h1f * t1.y);
-            ph[e] = pack_bf16(h0f * t0.x + l0 * t0.y, h1f * t1.x + l1 * t1.y);
-          }
+    for (int it = 0; it < VIT; ++it) {         // V rows into LDS
+      const int item = tid + it * 256;
+      const int ch = item % (D / 8), hl = (item / (D / 8)) % nh, key = item / ((D / 8) * nh);
+      if (item < nh * KB * (D / 8)) v_s[hl][key][ch] = v_reg[it];
+    }
+    __syncthreads();                           // cs_s and v_s ready
+#pragma unroll
+    for (int it = 0; it < KIT; ++it) {
+      const int item = tid + it * 256;
+      if (item >= nh * KB * (HALF / 8)) break;
+      const int c0 = (item % (HALF / 8)) * 8, hl = (item / (HALF / 8)) % nh, key = item / ((HALF / 8) * nh);
+      uint4 lo4 = k_lo[it], hi4 = k_hi[it];
+      if (rope && key0 + key < n_b) {
+        const float2* t = &cs_s[key][c0];
+        unsigned* pl = reinterpret_cast<unsigned*>(&lo4);
+        unsigned* ph = reinterpret_cast<unsigned*>(&hi4);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const float2 t0 = t[2 * e], t1 = t[2 * e + 1];
+          const float l0 = bf16_lo(pl[e]), l1 = bf16_hi(pl[e]);
+          const float h0f = bf16_lo(ph[e]), h1f = bf16_hi(ph[e]);
+          pl[e] = pack_bf16(l0 * t0.x - h0f * t0.y, l1 * t1.x - h1f * t1.y);
+          ph[e] = pack_bf16(h0f * t0.x + l0 * t0.y, h1f * t1.x + l1 * t1.y);
         }
       }
       // operand order: inside a block of 32 keys, chunk (t, hh, row) = features 16 t + 8 hh .. + 7
@@ -215,7 +234,6 @@ __global__ __launch_bounds__(256) void k_prep_kv(const int32_t* __restrict__ pla
       dst[(ci >> 1) * 64 + (ci & 1) * 32] = lo4;
       dst[((ci + D / 16) >> 1) * 64 + ((ci + D / 16) & 1) * 32] = hi4;
     }
-    __syncthreads();                           // v_s filled
     // V^T: a slab (16 keys) is [2][D][8]; element (hh, d, m) is key 8*(m/4) + 4*hh + (m%4) of the
     // slab at feature d.  Item = one 16-byte chunk (head, hh, d).
     constexpr int VROW = (D / 8 + 1) * 8;      // padded row length in elements
