@@ -207,3 +207,40 @@ def test_binding_refuses_host_and_strided_tensors():
     with pytest.raises(ValueError):
         ver.first_reject(torch.zeros(ver.sizes.total_segments, 2), 0.0)     # logits in host memory
     torch.cuda.synchronize()
+
+
+def _random_problem(rng):
+    B = int(rng.integers(1, 5))
+    P = [int(x) for x in rng.integers(0, 150, B)]
+    T = [int(x) for x in rng.integers(1, 400, B)]
+    K = [int(x) for x in rng.integers(0, 9, B)]
+    S = [int(rng.choice([1, 2, 5, 16, 31, 32, 33, 64, 70])) for _ in range(B)]
+    bounds = [sorted(int(x) for x in rng.integers(0, T[b] + 1, K[b])) for b in range(B)]
+    return wl.Problem(P, T, K, S, bounds)
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_random_plans_both_layouts(seed):
+    # seeded random structures (ragged batches, repeated and zero boundaries, segments shorter and longer
+    # than a tile), ten per case: dense mask, positions and judge rows bit-exact in both packings, the
+    # tile work list against the oracle's mask, and the readout
+    import dataclasses
+    rng = np.random.default_rng(9100 + seed)
+    for _ in range(10):
+        pr = _random_problem(rng)
+        check_plan(pr)
+        check_work_list(pr)
+        pri = dataclasses.replace(pr, layout=1)
+        w = wl.make_custom(pri, 4, 2, 64, dtype=torch.float32, seed=1)
+        ver = gc.make_verifier(pv, w, dense_mask=True)
+        ver.build_mask()
+        pos, ae, bs, jr = pv.pv_plan_export(ver.sizes, ver.plan)
+        torch.cuda.synchronize()
+        assert np.array_equal(ver.dense_mask.cpu().numpy(), gc.oracle_dense_mask_flat(pri))
+        opos, ojr = gc.oracle_plan_arrays(pri)
+        assert np.array_equal(pos.cpu().numpy().astype(np.int64), opos)
+        assert np.array_equal(jr.cpu().numpy().astype(np.int64), ojr)
+        thr = orc.margin_threshold(0.9)
+        for mode in (0, 1):
+            got = ver.first_reject(w.logits.cuda(), thr, mode).cpu().numpy()
+            assert np.array_equal(got, orc.first_reject(w.logits.numpy(), pr.num_segments, pr.boundaries, thr, mode))
