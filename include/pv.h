@@ -89,6 +89,8 @@ typedef struct {
   int32_t tile_m, tile_n;        /* query tokens per work item, keys per tile */
   int32_t n_short_rows;          /* rows with at most PV_SHORT_ROW_KEYS visible keys (see below) */
   int32_t layout;                /* the problem's layout */
+  int32_t n_seg_tiles;           /* query tiles that hold at least one segment row */
+  int32_t reserved;
 } pv_sizes;
 
 /* Host only: validates the problem and the head configuration and fills `out`.
@@ -130,6 +132,22 @@ pv_status pv_masked_attention(const pv_sizes* sizes, const void* plan_dev, const
                               const void* k, const void* v, void* out, float* lse,
                               int32_t out_dtype, float softmax_scale, float rope_theta,
                               void* workspace, int64_t workspace_bytes, void* stream);
+
+/* The same attention for the rows of the segments only ("extend" use: the prompt and draft rows
+ * were evaluated by an earlier pass, e.g. the full-answer verification, and only the K*S judge rows
+ * are wanted).  Arguments as for pv_masked_attention, bf16 inputs only (PV_ERR_DTYPE otherwise).
+ * K and V must still hold every token (the keys of prompt and draft are what the segments attend
+ * to); the Q rows of prompt and draft tokens are not read.  Writes `out` (and `lse`) for segment
+ * rows only and leaves all other rows untouched.  Few, long work items are split along the keys
+ * into pieces that run in parallel and are merged afterwards, with partial results in the
+ * workspace (attn_workspace_bytes covers them); every segment row gets the value
+ * pv_masked_attention gives it, up to the rounding of that merge.
+ * Callers: a judge pass over a KV prefix that already exists ("Parallel partial verify" after
+ * "Full verify", or the periodic premature verification of appendix "Full pipeline"). */
+pv_status pv_segment_attention(const pv_sizes* sizes, const void* plan_dev, const void* q,
+                               const void* k, const void* v, void* out, float* lse,
+                               int32_t out_dtype, float softmax_scale, float rope_theta,
+                               void* workspace, int64_t workspace_bytes, void* stream);
 
 /* Readout.  Verdict of segment k is Correct iff l_C >= l_I and l_C - l_I >= margin_threshold
  * (margin_threshold = ln(tau / (1 - tau)) makes this the two-way-confidence rule p_2w >= tau),

@@ -41,7 +41,8 @@ class PvSizes(C.Structure):
                 ("attn_workspace_bytes", C.c_int64),
                 ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32),
                 ("in_dtype", C.c_int32), ("tile_m", C.c_int32), ("tile_n", C.c_int32),
-                ("n_short_rows", C.c_int32), ("layout", C.c_int32)]
+                ("n_short_rows", C.c_int32), ("layout", C.c_int32),
+                ("n_seg_tiles", C.c_int32), ("reserved", C.c_int32)]
 
 
 PV_MAX_SHORT_CHUNKS = 8
@@ -68,6 +69,7 @@ def _load() -> C.CDLL:
     lib.pv_masked_attention.argtypes = [P(PvSizes), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                         C.c_void_p, C.c_void_p, C.c_int32, C.c_float, C.c_float,
                                         C.c_void_p, C.c_int64, C.c_void_p]
+    lib.pv_segment_attention.argtypes = lib.pv_masked_attention.argtypes
     lib.pv_first_reject.argtypes = [P(PvSizes), C.c_void_p, C.c_void_p, C.c_double, C.c_int32,
                                     C.c_void_p, C.c_void_p]
     lib.pv_plan_export.argtypes = [P(PvSizes), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
@@ -79,7 +81,7 @@ def _load() -> C.CDLL:
     lib.pv_profile_enable.argtypes = [C.c_int32]
     lib.pv_profile_read.argtypes = [P(C.c_float)]
     lib.pv_profile_read_all.argtypes = [P(C.c_float), C.c_int32, P(C.c_int32)]
-    for name in ("pv_query_sizes", "pv_build_mask", "pv_masked_attention", "pv_first_reject",
+    for name in ("pv_query_sizes", "pv_build_mask", "pv_masked_attention", "pv_segment_attention", "pv_first_reject",
                  "pv_plan_export", "pv_profile_enable", "pv_profile_read", "pv_profile_read_all",
                  "pv_last_hip_error",
                  "pv_judge_logits", "pv_decide"):
@@ -162,7 +164,7 @@ def pv_build_mask(problem: HostProblem, sizes: PvSizes, plan: torch.Tensor,
 def pv_masked_attention(sizes: PvSizes, plan: torch.Tensor, q: torch.Tensor, k: torch.Tensor,
                         v: torch.Tensor, out: torch.Tensor, workspace: torch.Tensor,
                         lse: Optional[torch.Tensor] = None, softmax_scale: float = 0.0,
-                        rope_theta: float = 0.0) -> None:
+                        rope_theta: float = 0.0, segments_only: bool = False) -> None:
     want = torch.float32 if sizes.in_dtype == PV_F32 else torch.bfloat16
     if q.dtype != want or k.dtype != want or v.dtype != want:
         raise ValueError("q/k/v dtype does not match sizes.in_dtype")
@@ -178,10 +180,20 @@ def pv_masked_attention(sizes: PvSizes, plan: torch.Tensor, q: torch.Tensor, k: 
         out_dtype = PV_F32
     else:
         raise ValueError("out must be bf16 or fp32")
-    _check(lib.pv_masked_attention(C.byref(sizes), _ptr(plan), _ptr(q), _ptr(k), _ptr(v), _ptr(out),
-                                   _ptr(lse), out_dtype, softmax_scale, rope_theta, _ptr(workspace),
-                                   workspace.numel() * workspace.element_size(), _stream()),
-           "pv_masked_attention")
+    fn = lib.pv_segment_attention if segments_only else lib.pv_masked_attention
+    _check(fn(C.byref(sizes), _ptr(plan), _ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(lse), out_dtype,
+              softmax_scale, rope_theta, _ptr(workspace), workspace.numel() * workspace.element_size(),
+              _stream()),
+           "pv_segment_attention" if segments_only else "pv_masked_attention")
+
+
+def pv_segment_attention(sizes: PvSizes, plan: torch.Tensor, q: torch.Tensor, k: torch.Tensor,
+                         v: torch.Tensor, out: torch.Tensor, workspace: torch.Tensor,
+                         lse: Optional[torch.Tensor] = None, softmax_scale: float = 0.0,
+                         rope_theta: float = 0.0) -> None:
+    """Rows of the segments only; every other row of `out` / `lse` is left as it is."""
+    pv_masked_attention(sizes, plan, q, k, v, out, workspace, lse, softmax_scale, rope_theta,
+                        segments_only=True)
 
 
 def pv_first_reject(sizes: PvSizes, plan: torch.Tensor, logits: torch.Tensor, margin_threshold: float,
@@ -297,6 +309,10 @@ class Verifier:
         if out is None:
             out = torch.empty_like(q)
         pv_masked_attention(self.sizes, self.plan, q, k, v, out, self.workspace, lse, softmax_scale, rope_theta)
+        return out
+
+    def segment_attention(self, q, k, v, out, lse=None, softmax_scale: float = 0.0, rope_theta: float = 0.0):
+        pv_segment_attention(self.sizes, self.plan, q, k, v, out, self.workspace, lse, softmax_scale, rope_theta)
         return out
 
     def first_reject(self, logits, margin_threshold: float, mode: int = 0):

@@ -21,7 +21,8 @@ static inline pv_status hip_fail(hipError_t e) {
 static inline int64_t align_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
 
 void plan_layout(int batch, int64_t total_tokens, int64_t total_segments, int64_t n_q_tiles,
-                 int64_t padded_keys, int64_t n_short_rows, int layout, PlanHeader* h) {
+                 int64_t padded_keys, int64_t n_short_rows, int layout, int64_t n_seg_tiles,
+                 PlanHeader* h) {
   std::memset(h, 0, sizeof(*h));
   h->magic = kPlanMagic;
   h->batch = batch;
@@ -33,6 +34,7 @@ void plan_layout(int batch, int64_t total_tokens, int64_t total_segments, int64_
   h->padded_keys = (int32_t)padded_keys;
   h->n_short_rows = (int32_t)n_short_rows;
   h->layout = layout;
+  h->n_seg_tiles = (int32_t)n_seg_tiles;
   int64_t o = sizeof(PlanHeader) / 4;
   auto take = [&](int64_t n) { int64_t r = o; o = align_up(o + n, 4); return (int32_t)r; };
   h->off_prompt = take(batch);
@@ -46,6 +48,7 @@ void plan_layout(int batch, int64_t total_tokens, int64_t total_segments, int64_
   h->off_mask_start = take(2 * (int64_t)(batch + 1));
   h->off_bounds = take(total_segments);
   h->off_short = take(n_short_rows);
+  h->off_segtile_start = take(batch + 1);
   h->off_device_begin = (int32_t)o;
   h->off_pos = take(total_tokens);
   h->off_aend = take(total_tokens);
@@ -54,12 +57,24 @@ void plan_layout(int batch, int64_t total_tokens, int64_t total_segments, int64_
   h->off_tiles = take(n_q_tiles * 8);
   h->off_work = take(n_q_tiles * 8);
   h->off_map = layout == PV_LAYOUT_INTERLEAVED ? take(total_tokens) : 0;
+  h->off_segwork = take(n_seg_tiles * 8);
   h->total_ints = (int32_t)o;
 }
 
-AttnWorkspace attn_workspace_layout(int64_t total_tokens, int64_t padded_keys, int hkv, int d,
-                                    int in_dtype) {
+// Pieces per work item of the segment-only call: enough to give every workgroup slot of the chip
+// (256 compute units x 2) an item, at most 8.
+static int segment_split(int64_t n_seg_tiles, int hkv) {
+  const int64_t items = n_seg_tiles * hkv;
+  if (items <= 0) return 1;
+  int64_t c = (512 + items - 1) / items;
+  return (int)(c < 1 ? 1 : (c > 8 ? 8 : c));
+}
+
+AttnWorkspace attn_workspace_layout(int64_t total_tokens, int64_t padded_keys, int64_t n_seg_tiles,
+                                    int hq, int hkv, int d, int in_dtype) {
   AttnWorkspace w;
+  w.off_part = 0;
+  w.split = 1;
   int64_t o = 0;
   w.off_cs = o;
   o = align_up(o + total_tokens * (d / 2) * 8, 256);
@@ -68,6 +83,9 @@ AttnWorkspace attn_workspace_layout(int64_t total_tokens, int64_t padded_keys, i
     o = align_up(o + (int64_t)hkv * padded_keys * d * 2, 256);
     w.off_vt = o;
     o = align_up(o + (int64_t)hkv * padded_keys * d * 2, 256);
+    w.split = segment_split(n_seg_tiles, hkv);
+    w.off_part = o;
+    if (w.split > 1) o = align_up(o + n_seg_tiles * hq * w.split * 32 * (d + 2) * 4, 256);
   } else {
     o = align_up(o + total_tokens * hkv * d * 4, 256);
     w.off_vt = o;
@@ -78,7 +96,7 @@ AttnWorkspace attn_workspace_layout(int64_t total_tokens, int64_t padded_keys, i
 
 struct Totals {
   int64_t tokens = 0, segments = 0, max_len = 0, q_tiles = 0, padded_keys = 0, mask_bytes = 0;
-  int64_t short_rows = 0;
+  int64_t short_rows = 0, seg_tiles = 0;
 };
 
 // Rows of request (P, T, S, boundaries) that see at most PV_SHORT_ROW_KEYS keys: the first causal
@@ -121,6 +139,7 @@ static pv_status validate_problem(const pv_problem* p, Totals* t) {
     t->tokens += n;
     t->max_len = n > t->max_len ? n : t->max_len;
     t->q_tiles += (n + kTileM - 1) / kTileM;
+    if (K > 0) t->seg_tiles += (n + kTileM - 1) / kTileM - (P + T) / kTileM;
     t->padded_keys += align_up(n, kTileN);
     t->mask_bytes += n * n;
   }
@@ -146,12 +165,15 @@ static void fill_sizes(const pv_problem* p, const Totals& t, int hq, int hkv, in
   s->n_q_tiles = t.q_tiles;
   s->padded_keys = t.padded_keys;
   PlanHeader h;
-  plan_layout(p->batch, t.tokens, t.segments, t.q_tiles, t.padded_keys, t.short_rows, p->layout, &h);
+  plan_layout(p->batch, t.tokens, t.segments, t.q_tiles, t.padded_keys, t.short_rows, p->layout,
+              t.seg_tiles, &h);
+  s->n_seg_tiles = (int32_t)t.seg_tiles;
   s->n_short_rows = (int32_t)t.short_rows;
   s->layout = p->layout;
   s->plan_bytes = (int64_t)h.total_ints * 4;
   s->dense_mask_bytes = t.mask_bytes;
-  s->attn_workspace_bytes = attn_workspace_layout(t.tokens, t.padded_keys, hkv, d, in_dtype).total;
+  s->attn_workspace_bytes =
+      attn_workspace_layout(t.tokens, t.padded_keys, t.seg_tiles, hq, hkv, d, in_dtype).total;
   s->n_q_heads = hq;
   s->n_kv_heads = hkv;
   s->head_dim = d;
@@ -169,13 +191,14 @@ static pv_status check_sizes(const pv_sizes* s, PlanHeader* h) {
     return PV_ERR_SHAPE;
   // the limits pv_query_sizes enforces: every index and offset of the plan stays inside int32
   if (s->batch > (1 << 20) || s->total_tokens > (1ll << 27) || s->padded_keys > (1ll << 27) ||
-      s->total_segments > s->total_tokens || s->n_q_tiles > s->total_tokens)
+      s->total_segments > s->total_tokens || s->n_q_tiles > s->total_tokens || s->n_seg_tiles < 0 ||
+      s->n_seg_tiles > s->n_q_tiles)
     return PV_ERR_SHAPE;
   if (validate_heads(s->n_q_heads, s->n_kv_heads, s->head_dim, s->in_dtype) != PV_OK)
     return PV_ERR_SHAPE;
   if (s->layout != PV_LAYOUT_APPENDED && s->layout != PV_LAYOUT_INTERLEAVED) return PV_ERR_SHAPE;
   plan_layout((int)s->batch, s->total_tokens, s->total_segments, s->n_q_tiles, s->padded_keys,
-              s->n_short_rows, s->layout, h);
+              s->n_short_rows, s->layout, s->n_seg_tiles, h);
   if (s->plan_bytes != (int64_t)h->total_ints * 4) return PV_ERR_SHAPE;
   return PV_OK;
 }
@@ -234,7 +257,8 @@ pv_status pv_build_mask(const pv_problem* problem, const pv_sizes* sizes, void* 
   if (sizes->batch != problem->batch || sizes->total_tokens != t.tokens ||
       sizes->total_segments != t.segments || sizes->n_q_tiles != t.q_tiles ||
       sizes->padded_keys != t.padded_keys || sizes->dense_mask_bytes != t.mask_bytes ||
-      sizes->n_short_rows != t.short_rows || sizes->layout != problem->layout)
+      sizes->n_short_rows != t.short_rows || sizes->layout != problem->layout ||
+      sizes->n_seg_tiles != t.seg_tiles)
     return PV_ERR_SHAPE;
   if (!plan_dev) return PV_ERR_NULL;
   if (plan_bytes < sizes->plan_bytes) return PV_ERR_WORKSPACE;
@@ -245,7 +269,7 @@ pv_status pv_build_mask(const pv_problem* problem, const pv_sizes* sizes, void* 
   std::vector<int32_t> img((size_t)h.off_device_begin, 0);
   std::memcpy(img.data(), &h, sizeof(h));
   const int B = problem->batch;
-  int64_t tok = 0, seg = 0, qt = 0, kp = 0, mk = 0, ns = 0;
+  int64_t tok = 0, seg = 0, qt = 0, kp = 0, mk = 0, ns = 0, sgt = 0;
   int64_t* mask_start = reinterpret_cast<int64_t*>(img.data() + h.off_mask_start);
   for (int b = 0; b <= B; ++b) {
     img[h.off_tok_start + b] = (int32_t)tok;
@@ -253,6 +277,7 @@ pv_status pv_build_mask(const pv_problem* problem, const pv_sizes* sizes, void* 
     img[h.off_qtile_start + b] = (int32_t)qt;
     img[h.off_kpad_start + b] = (int32_t)kp;
     mask_start[b] = mk;
+    img[h.off_segtile_start + b] = (int32_t)sgt;
     if (b == B) break;
     const int64_t P = problem->prompt_len[b], T = problem->draft_len[b],
                   K = problem->num_segments[b], S = problem->segment_len[b];
@@ -267,6 +292,7 @@ pv_status pv_build_mask(const pv_problem* problem, const pv_sizes* sizes, void* 
     tok += n;
     seg += K;
     qt += (n + kTileM - 1) / kTileM;
+    if (K > 0) sgt += (n + kTileM - 1) / kTileM - (P + T) / kTileM;
     kp += align_up(n, kTileN);
     mk += n * n;
   }
@@ -280,21 +306,24 @@ pv_status pv_build_mask(const pv_problem* problem, const pv_sizes* sizes, void* 
   return PV_OK;
 }
 
-pv_status pv_masked_attention(const pv_sizes* sizes, const void* plan_dev, const void* q,
-                              const void* k, const void* v, void* out, float* lse,
-                              int32_t out_dtype, float softmax_scale, float rope_theta,
-                              void* workspace, int64_t workspace_bytes, void* stream) {
+static pv_status attention_call(const pv_sizes* sizes, const void* plan_dev, const void* q,
+                                const void* k, const void* v, void* out, float* lse,
+                                int32_t out_dtype, float softmax_scale, float rope_theta,
+                                void* workspace, int64_t workspace_bytes, void* stream,
+                                bool segments_only) {
   PlanHeader h;
   pv_status st = check_sizes(sizes, &h);
   if (st != PV_OK) return st;
   if (!plan_dev || !q || !k || !v || !out || !workspace) return PV_ERR_NULL;
   if (out_dtype != PV_BF16 && out_dtype != PV_F32) return PV_ERR_DTYPE;
   if (sizes->in_dtype == PV_F32 && out_dtype != PV_F32) return PV_ERR_DTYPE;
+  if (segments_only && sizes->in_dtype != PV_BF16) return PV_ERR_DTYPE;
   if (!(softmax_scale >= 0.0f) || !std::isfinite(softmax_scale)) return PV_ERR_SHAPE;
   if (!(rope_theta >= 0.0f) || !std::isfinite(rope_theta)) return PV_ERR_SHAPE;
   const int hq = sizes->n_q_heads, hkv = sizes->n_kv_heads, d = sizes->head_dim;
   const AttnWorkspace wl =
-      attn_workspace_layout(sizes->total_tokens, sizes->padded_keys, hkv, d, sizes->in_dtype);
+      attn_workspace_layout(sizes->total_tokens, sizes->padded_keys, sizes->n_seg_tiles, hq, hkv, d,
+                            sizes->in_dtype);
   if (workspace_bytes < wl.total) return PV_ERR_WORKSPACE;
   if (misaligned(plan_dev) || misaligned(q) || misaligned(k) || misaligned(v) ||
       misaligned(out) || misaligned(workspace) || ((uintptr_t)lse & 3u))
@@ -329,11 +358,27 @@ pv_status pv_masked_attention(const pv_sizes* sizes, const void* plan_dev, const
       ev1 = pair[1];
     }
     e = launch_attn_bf16((const int32_t*)plan_dev, h, q, k, v, out, lse, hq, hkv, d, out_dtype,
-                         scale, freq, rope, (char*)workspace, wl, ev0, ev1, s);
+                         scale, freq, rope, (char*)workspace, wl, segments_only, ev0, ev1, s);
     if (e == hipSuccess && g_profile) ++g_ev_calls;
   }
   if (e != hipSuccess) return hip_fail(e);
   return PV_OK;
+}
+
+pv_status pv_masked_attention(const pv_sizes* sizes, const void* plan_dev, const void* q,
+                              const void* k, const void* v, void* out, float* lse,
+                              int32_t out_dtype, float softmax_scale, float rope_theta,
+                              void* workspace, int64_t workspace_bytes, void* stream) {
+  return attention_call(sizes, plan_dev, q, k, v, out, lse, out_dtype, softmax_scale, rope_theta,
+                        workspace, workspace_bytes, stream, false);
+}
+
+pv_status pv_segment_attention(const pv_sizes* sizes, const void* plan_dev, const void* q,
+                               const void* k, const void* v, void* out, float* lse,
+                               int32_t out_dtype, float softmax_scale, float rope_theta,
+                               void* workspace, int64_t workspace_bytes, void* stream) {
+  return attention_call(sizes, plan_dev, q, k, v, out, lse, out_dtype, softmax_scale, rope_theta,
+                        workspace, workspace_bytes, stream, true);
 }
 
 pv_status pv_first_reject(const pv_sizes* sizes, const void* plan_dev, const float* logits_dev,

@@ -26,6 +26,7 @@ struct ShortRowArgs {          // what the fp32 evaluation of the short rows nee
   int hq;
   float scale;
   bool out_f32;
+  bool seg_only;       // segment-only call: rows of prompt and draft tokens are left alone
 };
 
 // Rows with at most PV_SHORT_ROW_KEYS visible keys, in plain fp32 (the main kernel does not store
@@ -45,6 +46,7 @@ __device__ void short_row_block(const int32_t* __restrict__ plan, const PlanHead
   while (hi - lo > 1) { const int mid = (lo + hi) >> 1; if (ts[mid] <= g) lo = mid; else hi = mid; }
   const int base = ts[lo], i = g - base;
   const int a_end = plan[h.off_aend + g], b_start = plan[h.off_bstart + g];
+  if (a.seg_only && b_start == 0) return;      // a prompt or draft row (uniform over the workgroup)
   // Visible keys: [0, a_end) then [max(b_start, a_end), i]; at most PV_SHORT_ROW_KEYS of them.
   const int n_a = min(a_end, (int)PV_SHORT_ROW_KEYS);
   const int b0 = max(b_start, a_end);
@@ -260,7 +262,7 @@ __global__ __launch_bounds__(G * 64, 2) __attribute__((amdgpu_waves_per_eu(2))) 
     const int32_t* __restrict__ plan, PlanHeader h, const uint16_t* __restrict__ q,
     const uint16_t* __restrict__ krot, const uint16_t* __restrict__ vt,
     const float2* __restrict__ cs, void* __restrict__ out, float* __restrict__ lse, int hq, int hkv,
-    float qscale, bool rope, bool out_f32) {
+    float qscale, bool rope, bool out_f32, int split, float* __restrict__ part) {
   constexpr int KT = D / 16;            // MFMA steps along the feature dim for S^T
   constexpr int DB = D / 32;            // 32-feature blocks of O^T
   constexpr int CH32 = 32 * D / 8;      // 16-byte chunks per 32-key K (or V^T) slot
@@ -274,8 +276,14 @@ __global__ __launch_bounds__(G * 64, 2) __attribute__((amdgpu_waves_per_eu(2))) 
   // Layout: K ring (NS slots), then V^T ring (NS slots).  Step s lives in slot s % NS of each.
   __shared__ uint4 smem[2 * NS * CH32];
 
-  const int kvh = blockIdx.x % hkv;
-  const QTile tile = reinterpret_cast<const QTile*>(plan + h.off_work)[blockIdx.x / hkv];
+  // split == 0: the whole pass, one workgroup per entry of the work list and kv head.
+  // split >= 1: segment rows only, one workgroup per (tile holding segment rows, kv head, piece);
+  //             piece c of `split` covers the c-th share of the tile's listed key tiles.
+  const int piece = split ? (int)blockIdx.x % split : 0;
+  const int item = split ? (int)blockIdx.x / split : (int)blockIdx.x;   // (tile, kv head)
+  const int kvh = item % hkv;
+  const QTile tile =
+      reinterpret_cast<const QTile*>(plan + (split ? h.off_segwork : h.off_work))[item / hkv];
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int qrow = lane & 31, hh = lane >> 5;
   const int head = kvh * G + wave;
@@ -289,15 +297,23 @@ __global__ __launch_bounds__(G * 64, 2) __attribute__((amdgpu_waves_per_eu(2))) 
 
   // ---- key steps.  A key tile of the plan (64 keys) is two steps of 32 keys; tiles run over
   // [0, n_a) then [jb0, jb1).  The number of steps is even.
-  const int n_tiles = tile.n_a + (tile.jb1 - tile.jb0);
+  const int n_listed = tile.n_a + (tile.jb1 - tile.jb0);
+  const int kt0 = split ? piece * n_listed / split : 0;                 // first listed key tile
+  const int n_tiles = (split ? (piece + 1) * n_listed / split : n_listed) - kt0;
   const int n_steps = 2 * n_tiles;
   const int last = n_steps - 1;
+  // partial result of this wave (split > 1): float [32][D], then float2 [32] = (nmref, row sum)
+  float* part_o = part + ((int64_t)((int64_t)item * split + piece) * G + wave) * (32 * (D + 2));
+  if (n_steps == 0) {                       // fewer key tiles than pieces: this piece is empty
+    if (hh == 0) reinterpret_cast<float2*>(part_o + 32 * D)[qrow] = make_float2(0.0f, 0.0f);
+    return;
+  }
   // the plan lists the longest items first: they bound the run time, so their waves go first
   // wherever they share a SIMD with a shorter item
   if (blockIdx.x < gridDim.x / 4) __builtin_amdgcn_s_setprio(3);
   const int64_t head_base = ((int64_t)kvh * h.padded_keys + tile.kpad_base) * D;   // elements
   auto step_key0 = [&](int j) {           // first key (request-local) of step j
-    const int idx = j >> 1;
+    const int idx = (j >> 1) + kt0;
     const int jt = idx < tile.n_a ? idx : tile.jb0 + (idx - tile.n_a);
     return jt * 64 + (j & 1) * 32;
   };
@@ -566,7 +582,7 @@ __global__ __launch_bounds__(G * 64, 2) __attribute__((amdgpu_waves_per_eu(2))) 
   }
   __builtin_amdgcn_sched_barrier(0);
   load_k(min(1, last) % NS);
-  if (0 >= tile.n_full * 64) apply_mask(sA, step_key0(0));
+  if (step_key0(0) >= tile.n_full * 64) apply_mask(sA, step_key0(0));
   float rs0 = probs(sA, pA);
   wait_kv();
   qk(sB);                                            // S(1)
@@ -790,17 +806,24 @@ __global__ __launch_bounds__(G * 64, 2) __attribute__((amdgpu_waves_per_eu(2))) 
   const float l_tot = pair_sum(l_run);
   __syncthreads();                                    // every wave is done with the stages
   {
-    const float inv = 1.0f / l_tot;
+    const bool partial = split > 1;                   // this piece's result goes to the workspace
+    const float inv = partial ? 1.0f : 1.0f / l_tot;
     const int64_t tok0 = (int64_t)tile.tok_base + tile.t0;
     // rows with few visible keys are produced in fp32 by the preparation kernel: not stored here
-    // (lane r < 32 holds the descriptor of row r: one ballot gives the row mask to every lane)
+    // (lane r < 32 holds the descriptor of row r: one ballot gives the row mask to every lane);
+    // the segment-only call stores segment rows only (b_start > 0 marks them)
     const unsigned stored_rows = (unsigned)__builtin_amdgcn_ballot_w64(
-        valid && a_end + i_loc - b_start + 1 > PV_SHORT_ROW_KEYS);
-    auto stored = [&](int row) { return ((stored_rows >> row) & 1u) != 0; };
+        valid && a_end + i_loc - b_start + 1 > PV_SHORT_ROW_KEYS && (split == 0 || b_start > 0));
+    auto stored = [&](int row) { return partial || ((stored_rows >> row) & 1u) != 0; };
     constexpr int RS = 2 * D + 16;                    // row stride: 16 B of padding spreads the banks
     char* tr = reinterpret_cast<char*>(&smem[0]) + (size_t)wave * (32 * RS);
-    if (out_f32) {
-      float* op = reinterpret_cast<float*>(out);
+    // where row `row` of this wave's result goes, as fp32: the caller's tensor, or the partial tile
+    auto f32_row = [&](int row) {
+      return partial ? part_o + row * D
+                     : reinterpret_cast<float*>(out) + (caller_row(plan, h, tok0 + row) * hq + head) * D;
+    };
+    if (partial && hh == 0) reinterpret_cast<float2*>(part_o + 32 * D)[qrow] = make_float2(nmref, l_tot);
+    if (out_f32 || partial) {
 #pragma unroll
       for (int half = 0; half < 2; ++half) {
 #pragma unroll
@@ -817,9 +840,7 @@ __global__ __launch_bounds__(G * 64, 2) __attribute__((amdgpu_waves_per_eu(2))) 
         for (int it = 0; it < 32 * LPR / 64; ++it) {
           const int row = it * (64 / LPR) + lane / LPR, c = lane % LPR;
           const float4 w = *reinterpret_cast<const float4*>(tr + row * RS + c * 16);
-          if (stored(row))
-            *reinterpret_cast<float4*>(op + (caller_row(plan, h, tok0 + row) * hq + head) * D +
-                                       half * (D / 2) + c * 4) = w;
+          if (stored(row)) *reinterpret_cast<float4*>(f32_row(row) + half * (D / 2) + c * 4) = w;
         }
       }
     } else {
@@ -842,25 +863,100 @@ __global__ __launch_bounds__(G * 64, 2) __attribute__((amdgpu_waves_per_eu(2))) 
           *reinterpret_cast<uint4*>(op + (caller_row(plan, h, tok0 + row) * hq + head) * D + c * 8) = w;
       }
     }
-    if (lse && hh == 0 && valid && a_end + i_loc - b_start + 1 > PV_SHORT_ROW_KEYS)
+    if (lse && !partial && hh == 0 && stored(qrow))
       lse[(int64_t)head * h.total_tokens + caller_row(plan, h, g)] =
           (log2f(l_tot) - nmref) * 0.6931471805599453f;
   }
+}
+
+// Merge of the key pieces of the segment-only call.  One workgroup per (tile holding segment rows,
+// query head); 8 threads per row, each D/8 features.  Piece c holds, relative to its own reference
+// mref_c = -nmref_c (log2 units), the unnormalised O_c and the row sum l_c; with M = max mref_c over
+// the pieces that saw a key, O = sum_c 2^(mref_c - M) O_c / sum_c 2^(mref_c - M) l_c.
+template <int D>
+__global__ __launch_bounds__(256) void k_merge_pieces(const int32_t* __restrict__ plan, PlanHeader h,
+                                                      const float* __restrict__ part, int split,
+                                                      void* __restrict__ out, float* __restrict__ lse,
+                                                      int hq, int hkv, bool out_f32) {
+  constexpr int MAXSPLIT = 8, FPT = D / 8;           // features per thread
+  const int G = hq / hkv;
+  const int item = (int)blockIdx.x / G, hl = (int)blockIdx.x % G;     // (tile, kv head), head of group
+  const int kvh = item % hkv, head = kvh * G + hl;
+  const QTile tile = reinterpret_cast<const QTile*>(plan + h.off_segwork)[item / hkv];
+  const int row = threadIdx.x >> 3, sub = threadIdx.x & 7;
+  if (row >= tile.rows) return;
+  const int64_t g = (int64_t)tile.tok_base + tile.t0 + row;
+  const int a_end = plan[h.off_aend + g], b_start = plan[h.off_bstart + g];
+  const int i_loc = tile.t0 + row;
+  // segment rows only; rows with few keys come from the preparation kernel
+  if (b_start == 0 || a_end + i_loc - b_start + 1 <= PV_SHORT_ROW_KEYS) return;
+  float mref[MAXSPLIT], lsum[MAXSPLIT];
+  float M = -INFINITY;
+#pragma unroll
+  for (int c = 0; c < MAXSPLIT; ++c) {
+    mref[c] = 0.0f; lsum[c] = 0.0f;
+    if (c < split) {
+      const float* p = part + ((int64_t)((int64_t)item * split + c) * G + hl) * (32 * (D + 2));
+      const float2 ml = reinterpret_cast<const float2*>(p + 32 * D)[row];
+      mref[c] = -ml.x; lsum[c] = ml.y;
+      if (ml.y > 0.0f) M = fmaxf(M, mref[c]);
+    }
+  }
+  float acc[FPT];
+#pragma unroll
+  for (int e = 0; e < FPT; ++e) acc[e] = 0.0f;
+  float L = 0.0f;
+#pragma unroll
+  for (int c = 0; c < MAXSPLIT; ++c) {
+    if (c < split && lsum[c] > 0.0f) {               // a piece without a visible key holds nothing
+      const float w = exp2f(mref[c] - M);
+      L = fmaf(w, lsum[c], L);
+      const float* p = part + ((int64_t)((int64_t)item * split + c) * G + hl) * (32 * (D + 2)) +
+                       row * D + sub * FPT;
+#pragma unroll
+      for (int e = 0; e < FPT; e += 4) {
+        const float4 x = *reinterpret_cast<const float4*>(p + e);
+        acc[e] = fmaf(w, x.x, acc[e]); acc[e + 1] = fmaf(w, x.y, acc[e + 1]);
+        acc[e + 2] = fmaf(w, x.z, acc[e + 2]); acc[e + 3] = fmaf(w, x.w, acc[e + 3]);
+      }
+    }
+  }
+  const float inv = 1.0f / L;
+  const int64_t orow = (caller_row(plan, h, g) * hq + head) * D + sub * FPT;
+  if (out_f32) {
+    float* op = reinterpret_cast<float*>(out) + orow;
+#pragma unroll
+    for (int e = 0; e < FPT; e += 4)
+      *reinterpret_cast<float4*>(op + e) =
+          make_float4(acc[e] * inv, acc[e + 1] * inv, acc[e + 2] * inv, acc[e + 3] * inv);
+  } else {
+    uint16_t* op = reinterpret_cast<uint16_t*>(out) + orow;
+#pragma unroll
+    for (int e = 0; e < FPT; e += 4) {
+      uint2 w;
+      w.x = pack_bf16(acc[e] * inv, acc[e + 1] * inv);
+      w.y = pack_bf16(acc[e + 2] * inv, acc[e + 3] * inv);
+      *reinterpret_cast<uint2*>(op + e) = w;
+    }
+  }
+  if (lse && sub == 0)
+    lse[(int64_t)head * h.total_tokens + caller_row(plan, h, g)] = (log2f(L) + M) * 0.6931471805599453f;
 }
 
 template <int D, int G>
 static hipError_t launch_main(const int32_t* plan, const PlanHeader& h, const uint16_t* q,
                               const uint16_t* krot, const uint16_t* vt, const float2* cs, void* out,
                               float* lse, int hq, int hkv, float qscale, bool rope, bool out_f32,
-                              hipStream_t s) {
+                              int split, float* part, hipStream_t s) {
   dim3 grid;
-  if (!grid_1d((int64_t)h.n_q_tiles * hkv, G * 64, &grid)) return hipErrorInvalidConfiguration;
+  const int64_t blocks = split ? (int64_t)h.n_seg_tiles * hkv * split : (int64_t)h.n_q_tiles * hkv;
+  if (!grid_1d(blocks, G * 64, &grid)) return hipErrorInvalidConfiguration;
   if (rope)
     k_attn_bf16<D, G, true><<<grid, dim3(G * 64), 0, s>>>(plan, h, q, krot, vt, cs, out, lse, hq, hkv,
-                                                          qscale, rope, out_f32);
+                                                          qscale, rope, out_f32, split, part);
   else
     k_attn_bf16<D, G, false><<<grid, dim3(G * 64), 0, s>>>(plan, h, q, krot, vt, cs, out, lse, hq, hkv,
-                                                           qscale, rope, out_f32);
+                                                           qscale, rope, out_f32, split, part);
   return hipGetLastError();
 }
 
@@ -868,9 +964,9 @@ template <int D>
 static hipError_t dispatch_g(int G, const int32_t* plan, const PlanHeader& h, const uint16_t* q,
                              const uint16_t* krot, const uint16_t* vt, const float2* cs, void* out,
                              float* lse, int hq, int hkv, float qscale, bool rope, bool out_f32,
-                             hipStream_t s) {
+                             int split, float* part, hipStream_t s) {
   switch (G) {
-#define PV_CASE(GG) case GG: return launch_main<D, GG>(plan, h, q, krot, vt, cs, out, lse, hq, hkv, qscale, rope, out_f32, s);
+#define PV_CASE(GG) case GG: return launch_main<D, GG>(plan, h, q, krot, vt, cs, out, lse, hq, hkv, qscale, rope, out_f32, split, part, s);
     PV_CASE(1) PV_CASE(2) PV_CASE(3) PV_CASE(4) PV_CASE(5) PV_CASE(6) PV_CASE(7) PV_CASE(8)
 #undef PV_CASE
   }
@@ -880,33 +976,45 @@ static hipError_t dispatch_g(int G, const int32_t* plan, const PlanHeader& h, co
 hipError_t launch_attn_bf16(const int32_t* plan_dev, const PlanHeader& h, const void* q,
                             const void* k, const void* v, void* out, float* lse, int hq, int hkv,
                             int d, int out_dtype, float scale, const RopeFreq& freq, bool rope,
-                            char* ws, const AttnWorkspace& wl, hipEvent_t ev0, hipEvent_t ev1,
-                            hipStream_t s) {
+                            char* ws, const AttnWorkspace& wl, bool segments_only, hipEvent_t ev0,
+                            hipEvent_t ev1, hipStream_t s) {
+  if (segments_only && h.n_seg_tiles == 0) return hipSuccess;          // no segment anywhere
   float2* cs = reinterpret_cast<float2*>(ws + wl.off_cs);
   uint16_t* krot = reinterpret_cast<uint16_t*>(ws + wl.off_krot);
   uint16_t* vt = reinterpret_cast<uint16_t*>(ws + wl.off_vt);
+  float* part = reinterpret_cast<float*>(ws + wl.off_part);
   const uint16_t* kq = reinterpret_cast<const uint16_t*>(q);
   const uint16_t* kk = reinterpret_cast<const uint16_t*>(k);
   const uint16_t* kv = reinterpret_cast<const uint16_t*>(v);
+  const bool out_f32 = out_dtype == PV_F32;
   hipError_t e;
   {
     dim3 grid;
     if (!grid_1d((int64_t)(h.padded_keys / 16) * ((hkv + 1) / 2) + (int64_t)h.n_short_rows * hkv, 256, &grid))
       return hipErrorInvalidConfiguration;
     ShortRowArgs sr;
-    sr.q = kq; sr.out = out; sr.lse = lse; sr.hq = hq; sr.scale = scale; sr.out_f32 = out_dtype == PV_F32;
+    sr.q = kq; sr.out = out; sr.lse = lse; sr.hq = hq; sr.scale = scale; sr.out_f32 = out_f32;
+    sr.seg_only = segments_only;
     if (d == 64) k_prep_kv<64><<<grid, dim3(256), 0, s>>>(plan_dev, h, kk, kv, freq, cs, hkv, rope, krot, vt, sr);
     else k_prep_kv<128><<<grid, dim3(256), 0, s>>>(plan_dev, h, kk, kv, freq, cs, hkv, rope, krot, vt, sr);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
   }
   const float qscale = scale * 1.4426950408889634f;
-  const bool out_f32 = out_dtype == PV_F32;
+  const int split = segments_only ? wl.split : 0;
   if (ev0) { e = hipEventRecord(ev0, s); if (e != hipSuccess) return e; }
-  if (d == 64) e = dispatch_g<64>(hq / hkv, plan_dev, h, kq, krot, vt, cs, out, lse, hq, hkv, qscale, rope, out_f32, s);
-  else e = dispatch_g<128>(hq / hkv, plan_dev, h, kq, krot, vt, cs, out, lse, hq, hkv, qscale, rope, out_f32, s);
+  if (d == 64) e = dispatch_g<64>(hq / hkv, plan_dev, h, kq, krot, vt, cs, out, lse, hq, hkv, qscale, rope, out_f32, split, part, s);
+  else e = dispatch_g<128>(hq / hkv, plan_dev, h, kq, krot, vt, cs, out, lse, hq, hkv, qscale, rope, out_f32, split, part, s);
   if (e != hipSuccess) return e;
   if (ev1) { e = hipEventRecord(ev1, s); if (e != hipSuccess) return e; }
+  if (split > 1) {
+    dim3 grid;
+    if (!grid_1d((int64_t)h.n_seg_tiles * hq, 256, &grid)) return hipErrorInvalidConfiguration;
+    if (d == 64) k_merge_pieces<64><<<grid, dim3(256), 0, s>>>(plan_dev, h, part, split, out, lse, hq, hkv, out_f32);
+    else k_merge_pieces<128><<<grid, dim3(256), 0, s>>>(plan_dev, h, part, split, out, lse, hq, hkv, out_f32);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
   return hipSuccess;
 }
 

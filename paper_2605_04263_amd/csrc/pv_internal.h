@@ -36,9 +36,12 @@ struct PlanHeader {
   int32_t n_short_rows;
   int32_t layout;                                        // PV_LAYOUT_*
   int32_t off_map;                                       // [total_tokens], interleaved layout only
-  int32_t pad[2];
+  int32_t n_seg_tiles;                                   // query tiles with at least one segment row
+  int32_t off_segtile_start;                             // [B+1] first such tile of a request, counted over the batch
+  int32_t off_segwork;                                   // [n_seg_tiles][8] those tiles, request after request
+  int32_t pad[3];
 };
-static_assert(sizeof(PlanHeader) == 32 * 4, "PlanHeader must be 32 ints");
+static_assert(sizeof(PlanHeader) == 36 * 4, "PlanHeader must be 36 ints");
 
 // One-dimensional grid of `blocks` workgroups of `threads` threads.  A launch may not span 2^32
 // threads or more: a grid that large is reported as an error and never truncated.
@@ -74,10 +77,13 @@ struct AttnWorkspace {
   int64_t off_cs;      // float2 [total_tokens][D/2] (cos, sin)
   int64_t off_krot;    // bf16 path: [Hkv][padded_keys][D] bf16; fp32 path: [total_tokens][Hkv][D] float
   int64_t off_vt;      // bf16 path: V^T slabs, [Hkv][padded_keys/16][2][D][8] bf16
+  int64_t off_part;    // bf16 path, segment-only call: partial results of the key pieces, per
+                       // (segment tile, kv head, piece, head of the group): float [32][D] then float2 [32]
+  int split;           // pieces per work item of the segment-only call (1: no partial results)
   int64_t total;
 };
-AttnWorkspace attn_workspace_layout(int64_t total_tokens, int64_t padded_keys, int hkv, int d,
-                                    int in_dtype);
+AttnWorkspace attn_workspace_layout(int64_t total_tokens, int64_t padded_keys, int64_t n_seg_tiles,
+                                    int hq, int hkv, int d, int in_dtype);
 
 // --- launchers (each returns the hipError_t of its launches) ---
 // Uploads the host image (n_img ints at the start of the plan) and builds the device part.
@@ -98,12 +104,13 @@ hipError_t launch_attn_f32(const int32_t* plan_dev, const PlanHeader& h, const f
 hipError_t launch_attn_bf16(const int32_t* plan_dev, const PlanHeader& h, const void* q,
                             const void* k, const void* v, void* out, float* lse, int hq, int hkv,
                             int d, int out_dtype, float scale, const RopeFreq& freq, bool rope,
-                            char* ws, const AttnWorkspace& wl, hipEvent_t ev0, hipEvent_t ev1,
-                            hipStream_t s);
+                            char* ws, const AttnWorkspace& wl, bool segments_only, hipEvent_t ev0,
+                            hipEvent_t ev1, hipStream_t s);
 
 // Host-side layout of the plan; shared by pv_query_sizes and pv_build_mask.
 void plan_layout(int batch, int64_t total_tokens, int64_t total_segments, int64_t n_q_tiles,
-                 int64_t padded_keys, int64_t n_short_rows, int layout, PlanHeader* h);
+                 int64_t padded_keys, int64_t n_short_rows, int layout, int64_t n_seg_tiles,
+                 PlanHeader* h);
 
 }  // namespace pv
 #endif

@@ -124,8 +124,10 @@ __global__ __launch_bounds__(256) void k_plan_tokens(int32_t* plan, PlanHeader h
   plan_token(plan, plan, h, blockIdx.x * blockDim.x + threadIdx.x);
 }
 
-// Query tile t: the union of its rows' visible key sets, in key-tile units.
-__device__ inline QTile plan_tile(const int32_t* plan, const PlanHeader& h, int t) {
+// Query tile t: the union of its rows' visible key sets, in key-tile units.  *seg_slot is the
+// tile's place in the list of tiles that hold segment rows (request after request), -1 if it
+// holds none.
+__device__ inline QTile plan_tile(const int32_t* plan, const PlanHeader& h, int t, int* seg_slot) {
   const int b = find_owner(plan + h.off_qtile_start, h.batch, t);
   const Req r = load_req(plan, h, b);
   const int t0 = (t - plan[h.off_qtile_start + b]) * h.tile_m;
@@ -139,6 +141,7 @@ __device__ inline QTile plan_tile(const int32_t* plan, const PlanHeader& h, int 
   // first row, both non-decreasing in k because the boundaries are sorted.  The extremes over the
   // tile therefore sit at the first and last row of each kind.
   const int c = r.P + r.T, last = t0 + rows - 1;
+  *seg_slot = last >= c ? plan[h.off_segtile_start + b] + (t0 - c / h.tile_m * h.tile_m) / h.tile_m : -1;
   if (t0 < c) {
     min_prefix = t0 + 1;
     max_low = min(last, c - 1) + 1;
@@ -170,7 +173,12 @@ __device__ inline QTile plan_tile(const int32_t* plan, const PlanHeader& h, int 
 
 __global__ __launch_bounds__(256) void k_plan_tiles(int32_t* plan, PlanHeader h) {
   const int t = blockIdx.x * blockDim.x + threadIdx.x;
-  if (t < h.n_q_tiles) reinterpret_cast<QTile*>(plan + h.off_tiles)[t] = plan_tile(plan, h, t);
+  if (t < h.n_q_tiles) {
+    int seg_slot;
+    const QTile q = plan_tile(plan, h, t, &seg_slot);
+    reinterpret_cast<QTile*>(plan + h.off_tiles)[t] = q;
+    if (seg_slot >= 0) reinterpret_cast<QTile*>(plan + h.off_segwork)[seg_slot] = q;
+  }
 }
 
 // Small problems: the whole plan in one launch of one workgroup.  The host image arrives in the
@@ -188,9 +196,11 @@ __global__ __launch_bounds__(1024) void k_plan_small(int32_t* plan, PlanHeader h
   QTile mine;
   int my_cost = 0;
   if (tid < h.n_q_tiles) {
-    mine = plan_tile(img_s, h, tid);
+    int seg_slot;
+    mine = plan_tile(img_s, h, tid, &seg_slot);
     my_cost = mine.n_a + (mine.jb1 - mine.jb0);
     reinterpret_cast<QTile*>(plan + h.off_tiles)[tid] = mine;
+    if (seg_slot >= 0) reinterpret_cast<QTile*>(plan + h.off_segwork)[seg_slot] = mine;
     cost_s[tid] = my_cost;
   }
   __syncthreads();

@@ -190,3 +190,24 @@ def test_layout_is_validated_and_sized():
     tampered = pv.PvSizes.from_buffer_copy(s0)
     tampered.layout = pv.PV_LAYOUT_INTERLEAVED                         # plan_bytes no longer matches
     assert pv.lib.pv_first_reject(C.byref(tampered), fake, fake, 0.0, 0, fake, None) == pv.PV_ERR_SHAPE
+
+
+def test_segment_attention_validates_like_the_full_call():
+    p = pv.make_problem([4], [16], [2], [3], [5, 9])
+    st, s = q(p, 8, 2, 128)
+    assert st == pv.PV_OK and s.n_seg_tiles == 1                      # rows 20..25 sit in tile 0
+    fake = 0x1000
+    seg = lambda **kw: pv.lib.pv_segment_attention(
+        C.byref(kw.get("s", s)), fake, kw.get("q", fake), fake, fake, kw.get("out", fake), None,
+        kw.get("odt", pv.PV_BF16), 0.0, 0.0, fake, kw.get("wsb", s.attn_workspace_bytes), None)
+    assert seg(q=None) == pv.PV_ERR_NULL
+    assert seg(out=fake + 2) == pv.PV_ERR_ALIGN
+    assert seg(wsb=s.attn_workspace_bytes - 1) == pv.PV_ERR_WORKSPACE   # the partial results are part of it
+    st, s32 = q(p, 8, 2, 128, pv.PV_F32)
+    assert seg(s=s32, odt=pv.PV_F32, wsb=s32.attn_workspace_bytes) == pv.PV_ERR_DTYPE   # bf16 inputs only
+    tampered = pv.PvSizes.from_buffer_copy(s)
+    tampered.n_seg_tiles = 2
+    assert seg(s=tampered) == pv.PV_ERR_SHAPE
+    # a request without segments has no such tile; one whose segments start on a tile border has its own
+    assert q(pv.make_problem([4], [16], [0], [3], []), 8, 2, 128)[1].n_seg_tiles == 0
+    assert q(pv.make_problem([32], [32], [2], [40], [5, 9]), 8, 2, 128)[1].n_seg_tiles == 3
