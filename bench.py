@@ -188,6 +188,11 @@ def main() -> int:
     full_lg = torch.zeros(pr.batch, 2, device=dev)
     pol = pv.make_policy(thr, pv.margin_from_tau(0.90), pv.margin_from_tau(0.998), pv.margin_from_tau(0.95),
                          [pv.margin_from_tau(0.95)] * 2, 0.30, 2, 0.0)
+    # the same attention for the segment rows only (prompt and draft rows already evaluated by an
+    # earlier pass): key pieces in parallel plus a merge
+    seg_pairs = sum(pr.segment_len[b] * (pr.prompt_len[b] + p) + pr.segment_len[b] * (pr.segment_len[b] + 1) // 2
+                    for b in range(pr.batch) for p in pr.boundaries[b])
+    t_seg = timed(lambda: ver.segment_attention(q, k, v, out, rope_theta=w.rope_theta), n_b) if pr.total_segments else None
     t_judge = timed(lambda: ver.judge_logits(hid, w2), n_b)
     t_decide = timed(lambda: ver.decide(logits, full_lg, pol), n_b)
     del hid
@@ -210,6 +215,8 @@ def main() -> int:
         "breakdown_ms": {"pv_build_mask": t_build, "pv_masked_attention": t_attn, "pv_first_reject": t_read,
                          "attention_main_kernel": kernel_ms, "step_with_kernel_events": ms_per_step_events},
         "after_step_ms": {"pv_judge_logits_h4096": t_judge, "pv_decide": t_decide},
+        "segment_rows_only": {"pv_segment_attention_ms": t_seg, "unmasked_pairs": seg_pairs,
+                              "tflops": (4.0 * w.head_dim * w.n_q_heads * seg_pairs / (t_seg * 1e-3) / 1e12) if t_seg else None},
         "attn_tflops": eff_flops / (t_attn * 1e-3) / 1e12,
         "max_abs_output": float(out.float().abs().max()),   # bf16 output spacing grows with |o|
         "roofline": {"bound": "mfma", "kernel": "k_attn_bf16", "achieved": achieved,
