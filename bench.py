@@ -98,6 +98,9 @@ def main() -> int:
     ap.add_argument("--layout", default="appended", choices=["appended", "interleaved"],
                     help="row order of the packed tensors: segments after the draft, or each after its chunk")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="skip the untimed extra calls (decision calls, segment-only attention); used for "
+                         "profiles so that every launch of the main kernel is one of the timed path")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 256 MiB device copy (reference for HBM byte counters)")
     args = ap.parse_args()
@@ -192,9 +195,12 @@ def main() -> int:
     # earlier pass): key pieces in parallel plus a merge
     seg_pairs = sum(pr.segment_len[b] * (pr.prompt_len[b] + p) + pr.segment_len[b] * (pr.segment_len[b] + 1) // 2
                     for b in range(pr.batch) for p in pr.boundaries[b])
-    t_seg = timed(lambda: ver.segment_attention(q, k, v, out, rope_theta=w.rope_theta), n_b) if pr.total_segments else None
-    t_judge = timed(lambda: ver.judge_logits(hid, w2), n_b)
-    t_decide = timed(lambda: ver.decide(logits, full_lg, pol), n_b)
+    t_seg = t_judge = t_decide = None
+    if not args.no_extras:
+        if pr.total_segments:
+            t_seg = timed(lambda: ver.segment_attention(q, k, v, out, rope_theta=w.rope_theta), n_b)
+        t_judge = timed(lambda: ver.judge_logits(hid, w2), n_b)
+        t_decide = timed(lambda: ver.decide(logits, full_lg, pol), n_b)
     del hid
 
     achieved = eff_flops / (kernel_ms * 1e-3) / 1e12
