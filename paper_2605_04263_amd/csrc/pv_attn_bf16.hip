@@ -1,6 +1,6 @@
 // bf16 MFMA path of pv_masked_attention for gfx950.
 //
-// Two launches on the caller's stream:
+// Two launches on the caller's stream for the whole pass:
 //   k_prep_kv          cos/sin of every token's rotary angle (fp64 angle, fp32 result), K rotated
 //                      and written head-major in MFMA operand order, V written transposed in 16-key
 //                      slabs in MFMA operand order, so the main kernel stages both with plain
@@ -8,6 +8,9 @@
 //   k_attn_bf16        flash-style fused Q K^T / online softmax / P V.  One workgroup = one query
 //                      tile (32 tokens) x one kv head; wave w owns query head kvh*G + w, so the
 //                      G query heads of a GQA group share every K/V tile staged in LDS.
+// The segment-only call launches the same kernel over the tiles that hold segment rows, each cut
+// along the keys into pieces, and then
+//   k_merge_pieces     combines the pieces' unnormalised results.
 //
 // The product S^T = K Q^T is formed (keys x queries) so that a lane owns one query column:
 // row max / row sum are in-lane reductions plus one half-wave exchange, and the rescale factor
