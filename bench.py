@@ -7,7 +7,7 @@ whole step; `roofline` prices the main attention kernel alone against the bf16 M
 duration measured with HIP events on the launch stream inside the timed steps; `cpu_baseline`
 times the fp64 oracle on the host cores of the same box.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 8b|ragged|14b|70b|tiny]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 8b|8b_full_verify|ragged|14b|70b|tiny]
 """
 from __future__ import annotations
 

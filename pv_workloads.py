@@ -155,6 +155,15 @@ def make_8b(seed: int = 2000) -> Workload:
                     _judge_logits(rng, prob), 0.985, seed)
 
 
+def make_8b_full_verify(seed: int = 2500) -> Workload:
+    """The full-answer verification of the 8B-like shape: the same heads, prompt 512 + draft 2048, and no
+    segment at all (K = 0), i.e. one plain causal pass whose single judgment is read at the last token."""
+    prob = Problem([512], [2048], [0], [1], [[]])
+    q, k, v = _tensors(seed, prob.total_tokens, 32, 8, 128, torch.bfloat16)
+    return Workload("8b_full_verify", prob, 32, 8, 128, torch.bfloat16, 5e5, q, k, v,
+                    torch.zeros(0, 2, dtype=torch.float32), 0.998, seed)
+
+
 def make_ragged(seed: int = 3000, batch: int = 16) -> Workload:
     """8B-like heads, bf16; `batch` requests with prompt U[128,1024], draft U[512,4096],
     K U[4,32] segments of 32 tokens; boundaries K distinct sorted uniform on [16, T]."""
@@ -208,6 +217,7 @@ def make_70b(seed: int = 5000, batch: int = 4) -> Workload:
 WORKLOADS = {
     "tiny": make_tiny,
     "8b": make_8b,
+    "8b_full_verify": make_8b_full_verify,
     "ragged": make_ragged,
     "14b": make_14b,
     "70b": make_70b,
