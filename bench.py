@@ -26,7 +26,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0      # MI355X dense bf16 MFMA peak
 # HBM bytes per launch of the main kernel from two rocprofv3 --pmc runs (FETCH_SIZE KiB x 2.0, then
 # WRITE_SIZE KiB x 1.0; the factors are what a plain 256 MiB device copy reads on the same
 # counters).  Summaries are under profiles/.  Workloads not listed report null.
-MEASURED_TRAFFIC_BYTES = {"8b": int(25637.3 * 1024 * 2.0 + 24448 * 1024 * 1.0)}
+MEASURED_TRAFFIC_BYTES = {"8b": int(25660.6 * 1024 * 2.0 + 24448 * 1024 * 1.0)}
 
 
 def unmasked_pairs(problem) -> int:
