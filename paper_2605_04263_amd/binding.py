@@ -42,7 +42,7 @@ class PvSizes(C.Structure):
                 ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32),
                 ("in_dtype", C.c_int32), ("tile_m", C.c_int32), ("tile_n", C.c_int32),
                 ("n_short_rows", C.c_int32), ("layout", C.c_int32),
-                ("n_seg_tiles", C.c_int32), ("reserved", C.c_int32)]
+                ("n_seg_tiles", C.c_int32), ("n_quads", C.c_int32)]
 
 
 PV_MAX_SHORT_CHUNKS = 8

@@ -22,7 +22,7 @@ static inline int64_t align_up(int64_t x, int64_t a) { return (x + a - 1) / a * 
 
 void plan_layout(int batch, int64_t total_tokens, int64_t total_segments, int64_t n_q_tiles,
                  int64_t padded_keys, int64_t n_short_rows, int layout, int64_t n_seg_tiles,
-                 PlanHeader* h) {
+                 int64_t n_quads, PlanHeader* h) {
   std::memset(h, 0, sizeof(*h));
   h->magic = kPlanMagic;
   h->batch = batch;
@@ -35,6 +35,7 @@ void plan_layout(int batch, int64_t total_tokens, int64_t total_segments, int64_
   h->n_short_rows = (int32_t)n_short_rows;
   h->layout = layout;
   h->n_seg_tiles = (int32_t)n_seg_tiles;
+  h->n_quads = (int32_t)n_quads;
   int64_t o = sizeof(PlanHeader) / 4;
   auto take = [&](int64_t n) { int64_t r = o; o = align_up(o + n, 4); return (int32_t)r; };
   h->off_prompt = take(batch);
@@ -49,6 +50,7 @@ void plan_layout(int batch, int64_t total_tokens, int64_t total_segments, int64_
   h->off_bounds = take(total_segments);
   h->off_short = take(n_short_rows);
   h->off_segtile_start = take(batch + 1);
+  h->off_quad_start = take(batch + 1);
   h->off_device_begin = (int32_t)o;
   h->off_pos = take(total_tokens);
   h->off_aend = take(total_tokens);
@@ -58,6 +60,7 @@ void plan_layout(int batch, int64_t total_tokens, int64_t total_segments, int64_
   h->off_work = take(n_q_tiles * 8);
   h->off_map = layout == PV_LAYOUT_INTERLEAVED ? take(total_tokens) : 0;
   h->off_segwork = take(n_seg_tiles * 8);
+  h->off_quadwork = take(n_quads * 8);
   h->total_ints = (int32_t)o;
 }
 
@@ -96,7 +99,7 @@ AttnWorkspace attn_workspace_layout(int64_t total_tokens, int64_t padded_keys, i
 
 struct Totals {
   int64_t tokens = 0, segments = 0, max_len = 0, q_tiles = 0, padded_keys = 0, mask_bytes = 0;
-  int64_t short_rows = 0, seg_tiles = 0;
+  int64_t short_rows = 0, seg_tiles = 0, quads = 0;
 };
 
 // Rows of request (P, T, S, boundaries) that see at most PV_SHORT_ROW_KEYS keys: the first causal
@@ -139,6 +142,7 @@ static pv_status validate_problem(const pv_problem* p, Totals* t) {
     t->tokens += n;
     t->max_len = n > t->max_len ? n : t->max_len;
     t->q_tiles += (n + kTileM - 1) / kTileM;
+    t->quads += ((n + kTileM - 1) / kTileM + 3) / 4;
     if (K > 0) t->seg_tiles += (n + kTileM - 1) / kTileM - (P + T) / kTileM;
     t->padded_keys += align_up(n, kTileN);
     t->mask_bytes += n * n;
@@ -166,8 +170,9 @@ static void fill_sizes(const pv_problem* p, const Totals& t, int hq, int hkv, in
   s->padded_keys = t.padded_keys;
   PlanHeader h;
   plan_layout(p->batch, t.tokens, t.segments, t.q_tiles, t.padded_keys, t.short_rows, p->layout,
-              t.seg_tiles, &h);
+              t.seg_tiles, t.quads, &h);
   s->n_seg_tiles = (int32_t)t.seg_tiles;
+  s->n_quads = (int32_t)t.quads;
   s->n_short_rows = (int32_t)t.short_rows;
   s->layout = p->layout;
   s->plan_bytes = (int64_t)h.total_ints * 4;
@@ -192,13 +197,13 @@ static pv_status check_sizes(const pv_sizes* s, PlanHeader* h) {
   // the limits pv_query_sizes enforces: every index and offset of the plan stays inside int32
   if (s->batch > (1 << 20) || s->total_tokens > (1ll << 27) || s->padded_keys > (1ll << 27) ||
       s->total_segments > s->total_tokens || s->n_q_tiles > s->total_tokens || s->n_seg_tiles < 0 ||
-      s->n_seg_tiles > s->n_q_tiles)
+      s->n_seg_tiles > s->n_q_tiles || s->n_quads < 1 || s->n_quads > s->n_q_tiles)
     return PV_ERR_SHAPE;
   if (validate_heads(s->n_q_heads, s->n_kv_heads, s->head_dim, s->in_dtype) != PV_OK)
     return PV_ERR_SHAPE;
   if (s->layout != PV_LAYOUT_APPENDED && s->layout != PV_LAYOUT_INTERLEAVED) return PV_ERR_SHAPE;
   plan_layout((int)s->batch, s->total_tokens, s->total_segments, s->n_q_tiles, s->padded_keys,
-              s->n_short_rows, s->layout, s->n_seg_tiles, h);
+              s->n_short_rows, s->layout, s->n_seg_tiles, s->n_quads, h);
   if (s->plan_bytes != (int64_t)h->total_ints * 4) return PV_ERR_SHAPE;
   return PV_OK;
 }
@@ -258,7 +263,7 @@ pv_status pv_build_mask(const pv_problem* problem, const pv_sizes* sizes, void* 
       sizes->total_segments != t.segments || sizes->n_q_tiles != t.q_tiles ||
       sizes->padded_keys != t.padded_keys || sizes->dense_mask_bytes != t.mask_bytes ||
       sizes->n_short_rows != t.short_rows || sizes->layout != problem->layout ||
-      sizes->n_seg_tiles != t.seg_tiles)
+      sizes->n_seg_tiles != t.seg_tiles || sizes->n_quads != t.quads)
     return PV_ERR_SHAPE;
   if (!plan_dev) return PV_ERR_NULL;
   if (plan_bytes < sizes->plan_bytes) return PV_ERR_WORKSPACE;
@@ -269,7 +274,7 @@ pv_status pv_build_mask(const pv_problem* problem, const pv_sizes* sizes, void* 
   std::vector<int32_t> img((size_t)h.off_device_begin, 0);
   std::memcpy(img.data(), &h, sizeof(h));
   const int B = problem->batch;
-  int64_t tok = 0, seg = 0, qt = 0, kp = 0, mk = 0, ns = 0, sgt = 0;
+  int64_t tok = 0, seg = 0, qt = 0, kp = 0, mk = 0, ns = 0, sgt = 0, qd = 0;
   int64_t* mask_start = reinterpret_cast<int64_t*>(img.data() + h.off_mask_start);
   for (int b = 0; b <= B; ++b) {
     img[h.off_tok_start + b] = (int32_t)tok;
@@ -278,6 +283,7 @@ pv_status pv_build_mask(const pv_problem* problem, const pv_sizes* sizes, void* 
     img[h.off_kpad_start + b] = (int32_t)kp;
     mask_start[b] = mk;
     img[h.off_segtile_start + b] = (int32_t)sgt;
+    img[h.off_quad_start + b] = (int32_t)qd;
     if (b == B) break;
     const int64_t P = problem->prompt_len[b], T = problem->draft_len[b],
                   K = problem->num_segments[b], S = problem->segment_len[b];
@@ -292,6 +298,7 @@ pv_status pv_build_mask(const pv_problem* problem, const pv_sizes* sizes, void* 
     tok += n;
     seg += K;
     qt += (n + kTileM - 1) / kTileM;
+    qd += ((n + kTileM - 1) / kTileM + 3) / 4;
     if (K > 0) sgt += (n + kTileM - 1) / kTileM - (P + T) / kTileM;
     kp += align_up(n, kTileN);
     mk += n * n;

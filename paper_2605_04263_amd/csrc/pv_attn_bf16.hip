@@ -256,7 +256,11 @@ __global__ __launch_bounds__(256) void k_prep_kv(const int32_t* __restrict__ pla
 // FOLD: the softmax scale (times log2 e) is folded into Q before its single bf16 rounding, which
 // is free when Q is rotated anyway.  Without rotation Q enters the MFMA exactly as given and the
 // scale multiplies the fp32 score inside the exponent instead.
-template <int D, int G, bool FOLD>
+// QT ("query-tile workgroups", G == 4 waves): the four waves are four consecutive query tiles of ONE
+// query head instead of the heads of a group; used for group sizes that would leave wave slots of
+// a compute unit empty.  `tile` is then the union descriptor of the four tiles (it drives the key
+// loop and the staging) and every wave loads, masks and stores with its own tile `mine`.
+template <int D, int G, bool FOLD, bool QT = false>
 __global__ __launch_bounds__(G * 64, 2) __attribute__((amdgpu_waves_per_eu(2))) void k_attn_bf16(
     const int32_t* __restrict__ plan, PlanHeader h, const uint16_t* __restrict__ q,
     const uint16_t* __restrict__ krot, const uint16_t* __restrict__ vt,
@@ -280,15 +284,31 @@ __global__ __launch_bounds__(G * 64, 2) __attribute__((amdgpu_waves_per_eu(2))) 
   //             piece c of `split` covers the c-th share of the tile's listed key tiles.
   const int piece = split ? (int)blockIdx.x % split : 0;
   const int item = split ? (int)blockIdx.x / split : (int)blockIdx.x;   // (tile, kv head)
-  const int kvh = item % hkv;
-  const QTile tile =
-      reinterpret_cast<const QTile*>(plan + (split ? h.off_segwork : h.off_work))[item / hkv];
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int wave_s = __builtin_amdgcn_readfirstlane(wave);      // wave index as a scalar
   const int qrow = lane & 31, hh = lane >> 5;
-  const int head = kvh * G + wave;
-  const bool valid = qrow < tile.rows;
-  const int64_t g = (int64_t)tile.tok_base + tile.t0 + qrow;
-  const int i_loc = valid ? tile.t0 + qrow : -1;
+  int kvh, head;
+  QTile tile, mine;
+  if constexpr (QT) {
+    static_assert(G == 4, "query-tile workgroups have four waves");
+    head = (int)blockIdx.x % hq;
+    kvh = head / (hq / hkv);
+    tile = reinterpret_cast<const QTile*>(plan + h.off_quadwork)[(int)blockIdx.x / hq];
+    mine = tile;                              // a wave without a tile of its own: no row, never masks
+    mine.t0 = tile.t0 + 32 * wave_s;
+    mine.rows = 0;
+    mine.n_full = 1 << 24;
+    if (32 * wave_s < tile.rows)              // tile.n_full: index of the group's first tile
+      mine = reinterpret_cast<const QTile*>(plan + h.off_tiles)[tile.n_full + wave_s];
+  } else {
+    kvh = item % hkv;
+    head = kvh * G + wave;
+    tile = reinterpret_cast<const QTile*>(plan + (split ? h.off_segwork : h.off_work))[item / hkv];
+    mine = tile;
+  }
+  const bool valid = qrow < mine.rows;
+  const int64_t g = (int64_t)mine.tok_base + mine.t0 + qrow;
+  const int i_loc = valid ? mine.t0 + qrow : -1;
   int a_end = 0, b_start = 0;
   if (valid) { a_end = plan[h.off_aend + g]; b_start = plan[h.off_bstart + g]; }
 
@@ -319,7 +339,6 @@ __global__ __launch_bounds__(G * 64, 2) __attribute__((amdgpu_waves_per_eu(2))) 
   // Direct global->LDS staging: a wave instruction moves 64 consecutive 16-byte chunks, lane l
   // landing at chunk (base + l).  Both workspaces are already in MFMA operand order, so a slot is
   // a plain copy and operand reads are linear (lane l reads chunk l of its k-step: no conflicts).
-  const int wave_s = __builtin_amdgcn_readfirstlane(wave);      // wave index as a scalar
   constexpr int NREP = (CH32 / 64 + G - 1) / G;                  // staging instructions per wave
   const unsigned lane16 = (unsigned)lane * 16;
   const unsigned smem_base =
@@ -481,13 +500,26 @@ __global__ __launch_bounds__(G * 64, 2) __attribute__((amdgpu_waves_per_eu(2))) 
       const int R = P >> 4, pos = P & 15;
       const int Pg = (R << 4) + (pos ^ (R & 15));     // global chunk that lands at LDS chunk P
       const int row = Pg / CPR, ch = Pg % CPR;
-      const int hl = row >> 5, tok = min(row & 31, rows_m1);
-      const uint16_t* src = q + (caller_row(plan, h, tok0 + tok) * hq + kvh * G + hl) * D + (ch << 3);
+      // rows [32 hl, 32 hl + 32) of the area: head hl of the group, or (QT) tile hl of this head
+      const int hl = row >> 5;
+      const int tok = QT ? min(32 * hl + (row & 31), rows_m1) : min(row & 31, rows_m1);
+      const int src_head = QT ? head : kvh * G + hl;
+      const uint16_t* src = q + (caller_row(plan, h, tok0 + tok) * hq + src_head) * D + (ch << 3);
       __builtin_amdgcn_global_load_lds(
           (const __attribute__((address_space(1))) void*)src,
           (__attribute__((address_space(3))) void*)(uintptr_t)(q_area + c * 1024), 16, 0, 0);
     }
-    if (FOLD) {
+    // cos/sin rows: one set for the whole workgroup through LDS, or (QT: four times as many rows)
+    // every lane's own 16-byte pieces straight from the table
+    uint4 cs_own[QT && FOLD ? (KT / 2) * 4 : 1];
+    if constexpr (QT && FOLD) {
+      const uint4* row = reinterpret_cast<const uint4*>(cs + (tok0 + min(32 * wave_s + qrow, rows_m1)) * (D / 2));
+#pragma unroll
+      for (int t = 0; t < KT / 2; ++t)
+#pragma unroll
+        for (int k2 = 0; k2 < 4; ++k2) cs_own[t * 4 + k2] = row[8 * t + 4 * hh + k2];
+    }
+    if (FOLD && !QT) {
 #pragma unroll
       for (int n = 0; n < (CSCH / 64 + G - 1) / G; ++n) {
         const int c = wave_s + n * G;
@@ -522,7 +554,8 @@ __global__ __launch_bounds__(G * 64, 2) __attribute__((amdgpu_waves_per_eu(2))) 
       for (int t = 0; t < KT / 2; ++t) {
 #pragma unroll
         for (int k2 = 0; k2 < 4; ++k2) {
-          const uint4 w = cs_lds[swz(qrow * CSR + 8 * t + 4 * hh + k2)];
+          const uint4 w = (QT && FOLD) ? cs_own[(QT && FOLD) ? t * 4 + k2 : 0]
+                                       : cs_lds[swz(qrow * CSR + 8 * t + 4 * hh + k2)];
           const float c0 = __uint_as_float(w.x), s0r = __uint_as_float(w.y);
           const float c1 = __uint_as_float(w.z), s1r = __uint_as_float(w.w);
           const float lo0 = x[t][2 * k2], hi0 = x[t + KT / 2][2 * k2];
@@ -581,7 +614,7 @@ __global__ __launch_bounds__(G * 64, 2) __attribute__((amdgpu_waves_per_eu(2))) 
   }
   __builtin_amdgcn_sched_barrier(0);
   load_k(min(1, last) % NS);
-  if (step_key0(0) >= tile.n_full * 64) apply_mask(sA, step_key0(0));
+  if (step_key0(0) >= mine.n_full * 64) apply_mask(sA, step_key0(0));
   float rs0 = probs(sA, pA);
   wait_kv();
   qk(sB);                                            // S(1)
@@ -618,7 +651,7 @@ __global__ __launch_bounds__(G * 64, 2) __attribute__((amdgpu_waves_per_eu(2))) 
     const bool have1 = !decltype(last_of_pair)::value || j + 1 <= last;
     if (have1) {
       const int key0 = step_key0(j + 1);
-      if (__builtin_expect(key0 >= tile.n_full * 64, 0)) apply_mask(s_in, key0);
+      if (__builtin_expect(key0 >= mine.n_full * 64, 0)) apply_mask(s_in, key0);
     }
     const int slot_ks = sj + 2 >= NS ? sj + 2 - NS : sj + 2;   // (j + 2) % NS
     const bf16x8 pfa = as_bf16x8(make_uint4(p_in[0], p_in[1], p_in[2], p_in[3]));
@@ -807,7 +840,7 @@ __global__ __launch_bounds__(G * 64, 2) __attribute__((amdgpu_waves_per_eu(2))) 
   {
     const bool partial = split > 1;                   // this piece's result goes to the workspace
     const float inv = partial ? 1.0f : 1.0f / l_tot;
-    const int64_t tok0 = (int64_t)tile.tok_base + tile.t0;
+    const int64_t tok0 = (int64_t)mine.tok_base + mine.t0;
     // rows with few visible keys are produced in fp32 by the preparation kernel: not stored here
     // (lane r < 32 holds the descriptor of row r: one ballot gives the row mask to every lane);
     // the segment-only call stores segment rows only (b_start > 0 marks them)
@@ -959,11 +992,36 @@ static hipError_t launch_main(const int32_t* plan, const PlanHeader& h, const ui
   return hipGetLastError();
 }
 
+// Workgroups of four query tiles of one head (see QT above): one per (group of tiles, query head).
+template <int D>
+static hipError_t launch_query_tiles(const int32_t* plan, const PlanHeader& h, const uint16_t* q,
+                                     const uint16_t* krot, const uint16_t* vt, const float2* cs,
+                                     void* out, float* lse, int hq, int hkv, float qscale, bool rope,
+                                     bool out_f32, hipStream_t s) {
+  dim3 grid;
+  if (!grid_1d((int64_t)h.n_quads * hq, 256, &grid)) return hipErrorInvalidConfiguration;
+  if (rope)
+    k_attn_bf16<D, 4, true, true><<<grid, dim3(256), 0, s>>>(plan, h, q, krot, vt, cs, out, lse, hq, hkv,
+                                                             qscale, rope, out_f32, 0, nullptr);
+  else
+    k_attn_bf16<D, 4, false, true><<<grid, dim3(256), 0, s>>>(plan, h, q, krot, vt, cs, out, lse, hq, hkv,
+                                                              qscale, rope, out_f32, 0, nullptr);
+  return hipGetLastError();
+}
+
+// Group sizes 4 and 8 fill the wave slots of a compute unit with one workgroup per (tile, kv head):
+// 2 x 4 or 1 x 8 waves, every K/V slot staged once for the whole group.  The other sizes would leave
+// slots empty (5 waves: one workgroup of 5 in 8 slots; 1 or 2 waves: two workgroups of 1 or 2), so
+// the whole pass runs them as workgroups of four query tiles per head instead.
+static bool use_query_tiles(int G, int split) { return split == 0 && G != 4 && G != 8; }
+
 template <int D>
 static hipError_t dispatch_g(int G, const int32_t* plan, const PlanHeader& h, const uint16_t* q,
                              const uint16_t* krot, const uint16_t* vt, const float2* cs, void* out,
                              float* lse, int hq, int hkv, float qscale, bool rope, bool out_f32,
                              int split, float* part, hipStream_t s) {
+  if (use_query_tiles(G, split))
+    return launch_query_tiles<D>(plan, h, q, krot, vt, cs, out, lse, hq, hkv, qscale, rope, out_f32, s);
   switch (G) {
 #define PV_CASE(GG) case GG: return launch_main<D, GG>(plan, h, q, krot, vt, cs, out, lse, hq, hkv, qscale, rope, out_f32, split, part, s);
     PV_CASE(1) PV_CASE(2) PV_CASE(3) PV_CASE(4) PV_CASE(5) PV_CASE(6) PV_CASE(7) PV_CASE(8)

@@ -39,7 +39,9 @@ struct PlanHeader {
   int32_t n_seg_tiles;                                   // query tiles with at least one segment row
   int32_t off_segtile_start;                             // [B+1] first such tile of a request, counted over the batch
   int32_t off_segwork;                                   // [n_seg_tiles][8] those tiles, request after request
-  int32_t pad[3];
+  int32_t n_quads;                                       // groups of four consecutive query tiles of a request
+  int32_t off_quad_start;                                // [B+1] first such group of a request
+  int32_t off_quadwork;                                  // [n_quads][8], per request last group first
 };
 static_assert(sizeof(PlanHeader) == 36 * 4, "PlanHeader must be 36 ints");
 
@@ -110,7 +112,7 @@ hipError_t launch_attn_bf16(const int32_t* plan_dev, const PlanHeader& h, const 
 // Host-side layout of the plan; shared by pv_query_sizes and pv_build_mask.
 void plan_layout(int batch, int64_t total_tokens, int64_t total_segments, int64_t n_q_tiles,
                  int64_t padded_keys, int64_t n_short_rows, int layout, int64_t n_seg_tiles,
-                 PlanHeader* h);
+                 int64_t n_quads, PlanHeader* h);
 
 }  // namespace pv
 #endif

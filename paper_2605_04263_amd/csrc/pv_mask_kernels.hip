@@ -171,6 +171,36 @@ __device__ inline QTile plan_tile(const int32_t* plan, const PlanHeader& h, int 
   return q;
 }
 
+// Group qd of four consecutive query tiles of a request (the last group of a request may hold
+// fewer): the union of their key-tile lists, for the launch whose workgroups take four query tiles
+// of one head.  Every wave of such a workgroup masks with its own tile's descriptor, so key tiles
+// that only some of the four need are simply fully masked for the others.  `n_full` of the result
+// carries the index of the group's first tile in the tile list instead.  *slot: the groups of a
+// request are listed last first (the last group has the longest key list).
+__device__ inline QTile plan_quad(const int32_t* plan, const PlanHeader& h, int qd, int* slot) {
+  const int b = find_owner(plan + h.off_quad_start, h.batch, qd);
+  const int q0 = plan[h.off_quad_start + b], nq = plan[h.off_quad_start + b + 1] - q0;
+  const int ql = qd - q0;
+  const int t_first = plan[h.off_qtile_start + b] + 4 * ql;
+  const int t_end = min(t_first + 4, plan[h.off_qtile_start + b + 1]);
+  int unused;
+  QTile u = plan_tile(plan, h, t_first, &unused);
+  for (int t = t_first + 1; t < t_end; ++t) {
+    const QTile q = plan_tile(plan, h, t, &unused);
+    u.rows += q.rows;
+    u.n_a = max(u.n_a, q.n_a);
+    if (q.jb1 > q.jb0) {
+      if (u.jb1 > u.jb0) { u.jb0 = min(u.jb0, q.jb0); u.jb1 = max(u.jb1, q.jb1); }
+      else { u.jb0 = q.jb0; u.jb1 = q.jb1; }
+    }
+  }
+  if (u.jb1 > u.jb0) { u.jb0 = max(u.jb0, u.n_a); u.jb1 = max(u.jb1, u.jb0); }
+  else { u.jb0 = u.n_a; u.jb1 = u.n_a; }
+  u.n_full = t_first;
+  *slot = q0 + (nq - 1 - ql);
+  return u;
+}
+
 __global__ __launch_bounds__(256) void k_plan_tiles(int32_t* plan, PlanHeader h) {
   const int t = blockIdx.x * blockDim.x + threadIdx.x;
   if (t < h.n_q_tiles) {
@@ -178,6 +208,11 @@ __global__ __launch_bounds__(256) void k_plan_tiles(int32_t* plan, PlanHeader h)
     const QTile q = plan_tile(plan, h, t, &seg_slot);
     reinterpret_cast<QTile*>(plan + h.off_tiles)[t] = q;
     if (seg_slot >= 0) reinterpret_cast<QTile*>(plan + h.off_segwork)[seg_slot] = q;
+  }
+  if (t < h.n_quads) {
+    int slot;
+    const QTile u = plan_quad(plan, h, t, &slot);
+    reinterpret_cast<QTile*>(plan + h.off_quadwork)[slot] = u;
   }
 }
 
@@ -201,6 +236,11 @@ __global__ __launch_bounds__(1024) void k_plan_small(int32_t* plan, PlanHeader h
     my_cost = mine.n_a + (mine.jb1 - mine.jb0);
     reinterpret_cast<QTile*>(plan + h.off_tiles)[tid] = mine;
     if (seg_slot >= 0) reinterpret_cast<QTile*>(plan + h.off_segwork)[seg_slot] = mine;
+    if (tid < h.n_quads) {
+      int slot;
+      const QTile u = plan_quad(img_s, h, tid, &slot);
+      reinterpret_cast<QTile*>(plan + h.off_quadwork)[slot] = u;
+    }
     cost_s[tid] = my_cost;
   }
   __syncthreads();
