@@ -109,6 +109,23 @@ def test_group_sizes_long_rows(group, d):
     check_full(w)
 
 
+# Group sizes other than 4 and 8 run as workgroups of four query tiles of one head: ragged batches whose
+# last group of tiles is short, segments shorter and longer than a tile, and tiles that straddle two
+# segments, where the four waves of a workgroup mask with different descriptors.
+@pytest.mark.parametrize("case", range(4))
+def test_query_tile_workgroups(case):
+    pr = [wl.Problem([3, 0, 7, 64], [200, 9, 333, 640], [3, 2, 0, 6], [5, 1, 4, 40],
+                     [[0, 70, 200], [4, 4], [], [32, 64, 64, 300, 500, 640]]),
+          wl.Problem([130], [1], [9], [33], [[0, 0, 1, 1, 1, 1, 1, 1, 1]]),
+          wl.Problem([0], [129], [1], [127], [[64]]),
+          wl.Problem([100, 100], [412, 28], [4, 4], [70, 70], [[10, 200, 300, 412], [0, 5, 28, 28]])][case]
+    group, d, theta = [(5, 128, 5e5), (3, 64, 0.0), (7, 128, 1e4), (2, 128, 5e5)][case]
+    w = wl.make_custom(pr, group * 2, 2, d, dtype=torch.bfloat16, rope_theta=theta, seed=500 + case)
+    check_full(w)
+    import dataclasses
+    check_full(wl.Workload(**{**w.__dict__, "problem": dataclasses.replace(pr, layout=1)}))
+
+
 def random_problem(rng):
     B = int(rng.integers(1, 4))
     P = [int(x) for x in rng.integers(0, 90, B)]

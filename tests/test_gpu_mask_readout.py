@@ -244,3 +244,54 @@ def test_random_plans_both_layouts(seed):
         for mode in (0, 1):
             got = ver.first_reject(w.logits.cuda(), thr, mode).cpu().numpy()
             assert np.array_equal(got, orc.first_reject(w.logits.numpy(), pr.num_segments, pr.boundaries, thr, mode))
+
+
+def check_quad_list(pr):
+    """Groups of four consecutive query tiles (the work items of group sizes other than 4 and 8): every
+    group of every request appears once, last group of a request first, and its key-tile list holds every
+    key tile that any of its rows can see."""
+    w = wl.make_custom(pr, 5, 1, 64, dtype=torch.float32, seed=1)
+    ver = gc.make_verifier(pv, w)
+    ver.build_mask()
+    torch.cuda.synchronize()
+    blob = ver.plan.view(torch.int32).cpu().numpy()
+    n_quads, off_quadwork = int(blob[33]), int(blob[35])        # header ints 33..35: n_quads, off_quad_start, off_quadwork
+    assert n_quads == ver.sizes.n_quads == sum(((pr.seq_len(b) + 31) // 32 + 3) // 4 for b in range(pr.batch))
+    quads = blob[off_quadwork:off_quadwork + 8 * n_quads].reshape(n_quads, 8)
+    tiles, _ = _work_list(ver)
+    cu = pr.token_offsets()
+    at = 0
+    tile0 = 0
+    for b in range(pr.batch):
+        n = pr.seq_len(b)
+        M = orc.dense_mask(pr.prompt_len[b], pr.draft_len[b], pr.segment_len[b], pr.boundaries[b])
+        nkt = (n + 63) // 64
+        Mp = np.zeros((n, nkt * 64), dtype=np.uint8)
+        Mp[:, :n] = M
+        n_tiles = (n + 31) // 32
+        nq = (n_tiles + 3) // 4
+        for pos in range(nq):
+            ql = nq - 1 - pos                                   # last group first
+            tok_base, t0, rows, first_tile, n_a, jb0, jb1, _ = (int(x) for x in quads[at + pos])
+            assert (tok_base, t0, rows) == (cu[b], 128 * ql, min(128, n - 128 * ql))
+            assert first_tile == tile0 + 4 * ql and int(tiles[first_tile][1]) == t0
+            any_vis = Mp[t0:t0 + rows].reshape(rows, nkt, 64).any(axis=(0, 2))
+            listed = np.zeros(nkt, dtype=bool)
+            listed[:n_a] = True
+            listed[jb0:jb1] = True
+            assert 0 <= n_a <= jb0 <= jb1 <= nkt
+            assert not (any_vis & ~listed).any(), (b, ql)
+        at += nq
+        tile0 += n_tiles
+
+
+@pytest.mark.parametrize("idx", range(len(EDGE_PROBLEMS)))
+def test_quad_list_edge_cases(idx):
+    check_quad_list(EDGE_PROBLEMS[idx])
+
+
+def test_quad_list_random_and_named():
+    rng = np.random.default_rng(77)
+    for _ in range(25):
+        check_quad_list(_random_problem(rng))
+    check_quad_list(wl.make("14b").problem)
