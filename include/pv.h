@@ -90,7 +90,8 @@ typedef struct {
   int32_t n_short_rows;          /* rows with at most PV_SHORT_ROW_KEYS visible keys (see below) */
   int32_t layout;                /* the problem's layout */
   int32_t n_seg_tiles;           /* query tiles that hold at least one segment row */
-  int32_t n_quads;               /* groups of four consecutive query tiles of a request */
+  int32_t n_quads;               /* groups of four consecutive query tiles of a request; 0 unless
+                                    Hq/Hkv is a group size whose kernels take them as work items */
 } pv_sizes;
 
 /* Host only: validates the problem and the head configuration and fills `out`.

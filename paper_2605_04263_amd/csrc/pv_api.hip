@@ -170,9 +170,9 @@ static void fill_sizes(const pv_problem* p, const Totals& t, int hq, int hkv, in
   s->padded_keys = t.padded_keys;
   PlanHeader h;
   plan_layout(p->batch, t.tokens, t.segments, t.q_tiles, t.padded_keys, t.short_rows, p->layout,
-              t.seg_tiles, t.quads, &h);
+              t.seg_tiles, group_uses_query_tiles(hq / hkv) ? t.quads : 0, &h);
   s->n_seg_tiles = (int32_t)t.seg_tiles;
-  s->n_quads = (int32_t)t.quads;
+  s->n_quads = h.n_quads;
   s->n_short_rows = (int32_t)t.short_rows;
   s->layout = p->layout;
   s->plan_bytes = (int64_t)h.total_ints * 4;
@@ -197,7 +197,7 @@ static pv_status check_sizes(const pv_sizes* s, PlanHeader* h) {
   // the limits pv_query_sizes enforces: every index and offset of the plan stays inside int32
   if (s->batch > (1 << 20) || s->total_tokens > (1ll << 27) || s->padded_keys > (1ll << 27) ||
       s->total_segments > s->total_tokens || s->n_q_tiles > s->total_tokens || s->n_seg_tiles < 0 ||
-      s->n_seg_tiles > s->n_q_tiles || s->n_quads < 1 || s->n_quads > s->n_q_tiles)
+      s->n_seg_tiles > s->n_q_tiles || s->n_quads < 0 || s->n_quads > s->n_q_tiles)
     return PV_ERR_SHAPE;
   if (validate_heads(s->n_q_heads, s->n_kv_heads, s->head_dim, s->in_dtype) != PV_OK)
     return PV_ERR_SHAPE;
@@ -263,7 +263,8 @@ pv_status pv_build_mask(const pv_problem* problem, const pv_sizes* sizes, void* 
       sizes->total_segments != t.segments || sizes->n_q_tiles != t.q_tiles ||
       sizes->padded_keys != t.padded_keys || sizes->dense_mask_bytes != t.mask_bytes ||
       sizes->n_short_rows != t.short_rows || sizes->layout != problem->layout ||
-      sizes->n_seg_tiles != t.seg_tiles || sizes->n_quads != t.quads)
+      sizes->n_seg_tiles != t.seg_tiles ||
+      sizes->n_quads != (group_uses_query_tiles(sizes->n_q_heads / sizes->n_kv_heads) ? t.quads : 0))
     return PV_ERR_SHAPE;
   if (!plan_dev) return PV_ERR_NULL;
   if (plan_bytes < sizes->plan_bytes) return PV_ERR_WORKSPACE;

@@ -1009,20 +1009,13 @@ static hipError_t launch_query_tiles(const int32_t* plan, const PlanHeader& h, c
   return hipGetLastError();
 }
 
-// Group sizes 4 and 8 fill the wave slots of a compute unit with one workgroup per (tile, kv head):
-// 2 x 4 or 1 x 8 waves, every K/V slot staged once for the whole group.  The other sizes leave
-// slots empty (5 waves: one workgroup of 5 in 8 slots; 1 or 2 waves: two workgroups of 1 or 2), so
-// the whole pass runs them as workgroups of four query tiles per head instead.  Measured on one
-// shape (6 656 tokens, 8 kv heads): faster for G = 1, 2, 3, 5, 6 (1.65x .. 1.06x); with 7 of 8 slots
-// used, staging K/V once per group wins again.
-static bool use_query_tiles(int G, int split) { return split == 0 && G != 4 && G < 7; }
 
 template <int D>
 static hipError_t dispatch_g(int G, const int32_t* plan, const PlanHeader& h, const uint16_t* q,
                              const uint16_t* krot, const uint16_t* vt, const float2* cs, void* out,
                              float* lse, int hq, int hkv, float qscale, bool rope, bool out_f32,
                              int split, float* part, hipStream_t s) {
-  if (use_query_tiles(G, split))
+  if (split == 0 && group_uses_query_tiles(G) && h.n_quads > 0)
     return launch_query_tiles<D>(plan, h, q, krot, vt, cs, out, lse, hq, hkv, qscale, rope, out_f32, s);
   switch (G) {
 #define PV_CASE(GG) case GG: return launch_main<D, GG>(plan, h, q, krot, vt, cs, out, lse, hq, hkv, qscale, rope, out_f32, split, part, s);

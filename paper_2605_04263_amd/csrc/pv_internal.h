@@ -61,6 +61,15 @@ __device__ inline int64_t caller_row(const int32_t* plan, const PlanHeader& h, i
   return h.layout == PV_LAYOUT_INTERLEAVED ? (int64_t)plan[h.off_map + g] : g;
 }
 
+// Group sizes 4 and 8 fill the wave slots of a compute unit with one workgroup per (tile, kv head):
+// 2 x 4 or 1 x 8 waves, every K/V slot staged once for the whole group.  The other sizes leave
+// slots empty (5 waves: one workgroup of 5 in 8 slots; 1 or 2 waves: two workgroups of 1 or 2), so
+// the whole pass runs them as workgroups of four query tiles per head instead.  Measured on one
+// shape (6 656 tokens, 8 kv heads): faster for G = 1, 2, 3, 5, 6 (1.65x .. 1.06x); with 7 of 8 slots
+// used, staging K/V once per group wins again.  The plan lists the groups of four tiles only for
+// these sizes (n_quads = 0 otherwise).
+inline bool group_uses_query_tiles(int G) { return G != 4 && G < 7; }
+
 // One query tile of the work list (8 ints).
 struct QTile {
   int32_t tok_base;    // first packed row of the request

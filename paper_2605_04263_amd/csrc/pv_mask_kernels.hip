@@ -236,12 +236,16 @@ __global__ __launch_bounds__(1024) void k_plan_small(int32_t* plan, PlanHeader h
     my_cost = mine.n_a + (mine.jb1 - mine.jb0);
     reinterpret_cast<QTile*>(plan + h.off_tiles)[tid] = mine;
     if (seg_slot >= 0) reinterpret_cast<QTile*>(plan + h.off_segwork)[seg_slot] = mine;
-    if (tid < h.n_quads) {
-      int slot;
-      const QTile u = plan_quad(img_s, h, tid, &slot);
-      reinterpret_cast<QTile*>(plan + h.off_quadwork)[slot] = u;
-    }
+
     cost_s[tid] = my_cost;
+  }
+  // the groups of four tiles go to the threads after those of the tiles; if the workgroup is too
+  // small for both, the first threads take them as well
+  const bool beside = h.n_q_tiles + h.n_quads <= 1024;
+  for (int qd = beside ? tid - h.n_q_tiles : tid; qd >= 0 && qd < h.n_quads; qd += 1024) {
+    int slot;
+    const QTile u = plan_quad(img_s, h, qd, &slot);
+    reinterpret_cast<QTile*>(plan + h.off_quadwork)[slot] = u;
   }
   __syncthreads();
   if (tid < h.n_q_tiles) {          // longest first, stable
