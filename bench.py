@@ -92,8 +92,10 @@ def cpu_baseline(w, eff_flops: float) -> dict:
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
+    # a step is ~0.1 ms: a few hundred warm-up steps let clocks and caches settle (20 are not enough:
+    # the step then reads 4 % slower), and the timed loops still finish in a fraction of a second
+    ap.add_argument("--steps", type=int, default=400)
+    ap.add_argument("--warmup", type=int, default=200)
     ap.add_argument("--workload", default="8b")
     ap.add_argument("--layout", default="appended", choices=["appended", "interleaved"],
                     help="row order of the packed tensors: segments after the draft, or each after its chunk")
