@@ -126,6 +126,12 @@ def test_query_tile_workgroups(case):
     check_full(wl.Workload(**{**w.__dict__, "problem": dataclasses.replace(pr, layout=1)}))
 
 
+def test_query_tile_workgroups_large_plan():
+    # more than 8192 tokens (the plan comes from the separate kernels), group size 5, sampled rows
+    pr = wl.Problem([100, 7], [9000, 300], [3, 2], [40, 5], [[10, 4000, 9000], [0, 300]])
+    check_sampled(wl.make_custom(pr, 10, 2, 128, dtype=torch.bfloat16, rope_theta=5e5, seed=520), n_random=48)
+
+
 def random_problem(rng):
     B = int(rng.integers(1, 4))
     P = [int(x) for x in rng.integers(0, 90, B)]

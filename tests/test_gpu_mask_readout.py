@@ -295,3 +295,5 @@ def test_quad_list_random_and_named():
     for _ in range(25):
         check_quad_list(_random_problem(rng))
     check_quad_list(wl.make("14b").problem)
+    # more than 8192 tokens: the plan is built by the separate kernels, not by the single-workgroup one
+    check_quad_list(wl.Problem([100, 7], [9000, 300], [3, 2], [40, 5], [[10, 4000, 9000], [0, 300]]))
