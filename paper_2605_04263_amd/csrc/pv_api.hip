@@ -48,7 +48,7 @@ void plan_layout(int batch, int64_t total_tokens, int64_t total_segments, int64_
   h->off_kpad_start = take(batch + 1);
   h->off_mask_start = take(2 * (int64_t)(batch + 1));
   h->off_bounds = take(total_segments);
-  h->off_short = take(n_short_rows);
+  h->off_short = take(4 * n_short_rows);
   h->off_segtile_start = take(batch + 1);
   h->off_quad_start = take(batch + 1);
   h->off_device_begin = (int32_t)o;
@@ -294,8 +294,17 @@ pv_status pv_build_mask(const pv_problem* problem, const pv_sizes* sizes, void* 
     img[h.off_nseg + b] = (int32_t)K;
     img[h.off_seglen + b] = (int32_t)S;
     for (int64_t k = 0; k < K; ++k) img[h.off_bounds + seg + k] = problem->boundaries[seg + k];
-    for_each_short_row(P, T, K, S, problem->boundaries + seg,
-                       [&](int64_t i) { img[h.off_short + ns++] = (int32_t)(tok + i); });
+    // A short row carries its descriptor with it (the same values the plan kernels write for the
+    // row), so that the blocks evaluating it start from one load instead of a chain of three.
+    for_each_short_row(P, T, K, S, problem->boundaries + seg, [&](int64_t i) {
+      int32_t* e = &img[h.off_short + 4 * ns++];
+      const int64_t c = P + T;
+      const int64_t k = i < c ? 0 : (i - c) / S;
+      e[0] = (int32_t)(tok + i);
+      e[1] = (int32_t)tok;
+      e[2] = i < c ? 0 : (int32_t)(P + problem->boundaries[seg + k]);
+      e[3] = i < c ? 0 : (int32_t)(c + k * S);
+    });
     tok += n;
     seg += K;
     qt += (n + kTileM - 1) / kTileM;

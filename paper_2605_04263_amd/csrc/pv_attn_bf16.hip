@@ -40,15 +40,13 @@ template <int D>
 __device__ void short_row_block(const int32_t* __restrict__ plan, const PlanHeader& h,
                                 const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
                                 const RopeFreq& f, int hkv, bool rope, const ShortRowArgs& a,
-                                int g, int kvh, float (*ks)[D], float (*vs)[D]) {
+                                int4 desc, int kvh, float (*ks)[D], float (*vs)[D]) {
   constexpr int HALF = D / 2;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int G = a.hq / hkv;
-  const int32_t* ts = plan + h.off_tok_start;
-  int lo = 0, hi = h.batch;
-  while (hi - lo > 1) { const int mid = (lo + hi) >> 1; if (ts[mid] <= g) lo = mid; else hi = mid; }
-  const int base = ts[lo], i = g - base;
-  const int a_end = plan[h.off_aend + g], b_start = plan[h.off_bstart + g];
+  // desc = (packed row, first row of its request, a_end, b_start), written by the host
+  const int g = desc.x, base = desc.y, i = g - base;
+  const int a_end = desc.z, b_start = desc.w;
   if (a.seg_only && b_start == 0) return;      // a prompt or draft row (uniform over the workgroup)
   // Visible keys: [0, a_end) then [max(b_start, a_end), i]; at most PV_SHORT_ROW_KEYS of them.
   const int n_a = min(a_end, (int)PV_SHORT_ROW_KEYS);
@@ -62,15 +60,40 @@ __device__ void short_row_block(const int32_t* __restrict__ plan, const PlanHead
       *hi_out = xh * t.x + xl * t.y;
     } else { *lo_out = xl; *hi_out = xh; }
   };
-  for (int item = tid; item < n * HALF; item += 256) {
+  // all loads of the pass are issued before any of them is used (fixed trip count, predicated)
+  constexpr int IT = PV_SHORT_ROW_KEYS * HALF / 256;
+  static_assert(IT * 256 == PV_SHORT_ROW_KEYS * HALF, "whole passes");
+  unsigned short k_lo[IT], k_hi[IT], v_lo[IT], v_hi[IT];
+  int pos_k[IT];
+#pragma unroll
+  for (int it = 0; it < IT; ++it) {
+    const int item = tid + it * 256;
     const int e = item / HALF, c = item % HALF;
     const int key = e < n_a ? e : b0 + (e - n_a);
-    const int tok = base + key;
+    const int tok = base + (e < n ? key : i);             // clamp to a valid row when predicated off
     const int64_t tok_row = caller_row(plan, h, tok);
-    rotate(k + (tok_row * hkv + kvh) * D, tok, c, &ks[e][c], &ks[e][c + HALF]);
+    const uint16_t* kr = k + (tok_row * hkv + kvh) * D;
     const uint16_t* vr = v + (tok_row * hkv + kvh) * D;
-    vs[e][c] = __uint_as_float((unsigned)vr[c] << 16);
-    vs[e][c + HALF] = __uint_as_float((unsigned)vr[c + HALF] << 16);
+    k_lo[it] = kr[c]; k_hi[it] = kr[c + HALF];
+    v_lo[it] = vr[c]; v_hi[it] = vr[c + HALF];
+    pos_k[it] = plan[h.off_pos + tok];
+  }
+#pragma unroll
+  for (int it = 0; it < IT; ++it) {
+    const int item = tid + it * 256;
+    const int e = item / HALF, c = item % HALF;
+    if (e < n) {
+      const float xl = __uint_as_float((unsigned)k_lo[it] << 16), xh = __uint_as_float((unsigned)k_hi[it] << 16);
+      float rl = xl, rh = xh;
+      if (rope) {
+        const float2 t = rotary_cos_sin(pos_k[it], f.inv_freq[c]);
+        rl = xl * t.x - xh * t.y;
+        rh = xh * t.x + xl * t.y;
+      }
+      ks[e][c] = rl; ks[e][c + HALF] = rh;
+      vs[e][c] = __uint_as_float((unsigned)v_lo[it] << 16);
+      vs[e][c + HALF] = __uint_as_float((unsigned)v_hi[it] << 16);
+    }
   }
   __syncthreads();
   const bool on = lane < HALF;
@@ -135,9 +158,10 @@ __global__ __launch_bounds__(256) void k_prep_kv(const int32_t* __restrict__ pla
   const int n_short_blocks = h.n_short_rows * hkv;
   if ((int)blockIdx.x < n_short_blocks) {      // one (short row, kv head) each
     const int idx = (int)blockIdx.x;
-    const int g = plan[h.off_short + idx / hkv], kvh = idx % hkv;
+    const int4 desc = reinterpret_cast<const int4*>(plan + h.off_short)[idx / hkv];
+    const int kvh = idx % hkv;
     float (*ks)[D] = reinterpret_cast<float (*)[D]>(&lds[0]);
-    short_row_block<D>(plan, h, k, v, f, hkv, rope, sr, g, kvh, ks, ks + PV_SHORT_ROW_KEYS);
+    short_row_block<D>(plan, h, k, v, f, hkv, rope, sr, desc, kvh, ks, ks + PV_SHORT_ROW_KEYS);
     return;
   }
   float2 (*cs_s)[HALF] = reinterpret_cast<float2 (*)[HALF]>(&lds[0]);                       // cos/sin of the block's tokens

@@ -27,7 +27,7 @@ struct PlanHeader {
   int32_t off_qtile_start, off_kpad_start;               // [B+1] each
   int32_t off_mask_start;                                // int64 [B+1] (8-byte aligned)
   int32_t off_bounds;                                    // [total_segments]
-  int32_t off_short;                                     // [n_short_rows] packed row indices
+  int32_t off_short;                                     // [n_short_rows][4]: packed row, first row of its request, a_end, b_start
   int32_t off_device_begin;
   int32_t off_pos, off_aend, off_bstart;                 // [total_tokens] each
   int32_t off_judge;                                     // [total_segments]
