@@ -52,14 +52,13 @@ __device__ void short_row_block(const int32_t* __restrict__ plan, const PlanHead
   const int n_a = min(a_end, (int)PV_SHORT_ROW_KEYS);
   const int b0 = max(b_start, a_end);
   const int n = min(n_a + max(i - b0 + 1, 0), (int)PV_SHORT_ROW_KEYS);
-  auto rotate = [&](const uint16_t* row, int tok, int c, float* lo_out, float* hi_out) {
-    const float xl = __uint_as_float((unsigned)row[c] << 16), xh = __uint_as_float((unsigned)row[c + HALF] << 16);
-    if (rope) {
-      const float2 t = rotary_cos_sin(plan[h.off_pos + tok], f.inv_freq[c]);
-      *lo_out = xl * t.x - xh * t.y;
-      *hi_out = xh * t.x + xl * t.y;
-    } else { *lo_out = xl; *hi_out = xh; }
-  };
+  // the query pair of this wave's first head and the row's position are requested up front as well
+  const bool on = lane < HALF;
+  const int c = on ? lane : 0;
+  const int64_t g_row = caller_row(plan, h, g);        // this row in q / out / lse
+  const uint16_t* q_first = a.q + (g_row * a.hq + kvh * G + min(wave, G - 1)) * D;
+  const unsigned short q_lo0 = q_first[c], q_hi0 = q_first[c + HALF];
+  const int pos_g = plan[h.off_pos + g];
   // all loads of the pass are issued before any of them is used (fixed trip count, predicated)
   constexpr int IT = PV_SHORT_ROW_KEYS * HALF / 256;
   static_assert(IT * 256 == PV_SHORT_ROW_KEYS * HALF, "whole passes");
@@ -96,13 +95,13 @@ __device__ void short_row_block(const int32_t* __restrict__ plan, const PlanHead
     }
   }
   __syncthreads();
-  const bool on = lane < HALF;
-  const int c = on ? lane : 0;
-  const int64_t g_row = caller_row(plan, h, g);        // this row in q / out / lse
+  const float2 t_g = rope ? rotary_cos_sin(pos_g, f.inv_freq[c]) : make_float2(1.0f, 0.0f);
   for (int hl = wave; hl < G; hl += 4) {
     const int head = kvh * G + hl;
-    float ql, qh;
-    rotate(a.q + (g_row * a.hq + head) * D, g, c, &ql, &qh);
+    const uint16_t* qr = a.q + (g_row * a.hq + head) * D;
+    const unsigned short q_lo = hl == wave ? q_lo0 : qr[c], q_hi = hl == wave ? q_hi0 : qr[c + HALF];
+    const float xl = __uint_as_float((unsigned)q_lo << 16), xh = __uint_as_float((unsigned)q_hi << 16);
+    const float ql = xl * t_g.x - xh * t_g.y, qh = xh * t_g.x + xl * t_g.y;
     float sc[PV_SHORT_ROW_KEYS];
     float m = -INFINITY;
 #pragma unroll
