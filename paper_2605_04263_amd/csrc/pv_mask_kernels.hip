@@ -216,18 +216,29 @@ __global__ __launch_bounds__(256) void k_plan_tiles(int32_t* plan, PlanHeader h)
   }
 }
 
-// Small problems: the whole plan in one launch of one workgroup.  The host image arrives in the
-// kernel arguments and is written first; the phases are separated by workgroup barriers.
+// Small problems: the whole plan in one launch.  The host image arrives in the kernel arguments, so
+// every workgroup has it without waiting for another: workgroup 0 writes it to the plan and builds the
+// tile lists (phases separated by workgroup barriers), the other workgroups share the per-token
+// arrays among them.  Nothing written by one workgroup is read by another inside the launch.
 constexpr int kSmallTokens = 8192, kSmallTiles = 1024;
 __global__ __launch_bounds__(1024) void k_plan_small(int32_t* plan, PlanHeader h, UploadChunk c,
                                                      int n_img) {
   __shared__ int cost_s[kSmallTiles];
   __shared__ int32_t img_s[kUploadInts];       // the request data is read from here, not from HBM
   const int tid = threadIdx.x;
-  for (int i = tid; i < n_img; i += 1024) { const int32_t x = c.v[i]; plan[i] = x; img_s[i] = x; }
+  const bool first = blockIdx.x == 0;
+  for (int i = tid; i < n_img; i += 1024) {
+    const int32_t x = c.v[i];
+    if (first) plan[i] = x;
+    img_s[i] = x;
+  }
   __syncthreads();
   const int n1 = h.total_tokens > h.total_segments ? h.total_tokens : h.total_segments;
-  for (int g = tid; g < n1; g += 1024) plan_token(plan, img_s, h, g);
+  if (gridDim.x == 1 || !first) {              // tokens: all workgroups but the first, if there are others
+    const int nb = gridDim.x == 1 ? 1 : (int)gridDim.x - 1, me = gridDim.x == 1 ? 0 : (int)blockIdx.x - 1;
+    for (int g = me * 1024 + tid; g < n1; g += nb * 1024) plan_token(plan, img_s, h, g);
+  }
+  if (!first) return;
   QTile mine;
   int my_cost = 0;
   if (tid < h.n_q_tiles) {
@@ -299,7 +310,8 @@ hipError_t launch_plan_kernels(int32_t* plan_dev, const PlanHeader& h, const int
     UploadChunk c;
     for (int i = 0; i < n_img; ++i) c.v[i] = host_ints[i];
     for (int i = n_img; i < kUploadInts; ++i) c.v[i] = 0;
-    k_plan_small<<<dim3(1), dim3(1024), 0, s>>>(plan_dev, h, c, n_img);
+    const int token_groups = (n1 + 1023) / 1024;                 // at most three extra workgroups
+    k_plan_small<<<dim3(1 + (token_groups < 3 ? token_groups : 3)), dim3(1024), 0, s>>>(plan_dev, h, c, n_img);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
   } else {
