@@ -13,8 +13,8 @@ calibration", "Parallel partial verify", "Adopted-prefix length"):
                     "Parallel Prefix Verification".
 * `positions`       rotary positions: prompt and draft count up from 0; suffix
                     copy k continues from the end of the prefix it judges, so
-                    that its judgment position "sees exactly the input" of a
-                    stand-alone run of (prefix, suffix).
+                    that its judgment position receives the same input as a
+                    stand-alone run of that prefix followed by the suffix.
 * `rope`            rotary embedding, half-split pairing.
 * `attention`       softmax(mask(Q K^T * scale)) V for one request, no tiling.
 * `*_interleaved`   the same pass in the packing of "Parallel partial verify": every suffix

@@ -37,31 +37,44 @@ def library_causal(q, k, v, G, scale):
     return o[0].permute(1, 0, 2).numpy()
 
 
+def library_causal_lse(q, k, G, scale):
+    """Natural-log softmax normaliser of every row of a stand-alone causal pass, [L, Hq]: library
+    matmul, library lower-triangular fill, torch.logsumexp (fp64)."""
+    tq = torch.from_numpy(q).permute(1, 0, 2)
+    tk = torch.from_numpy(np.repeat(k, G, axis=1)).permute(1, 0, 2)
+    s = torch.matmul(tq, tk.transpose(1, 2)) * scale                    # [Hq, L, L]
+    L = s.shape[-1]
+    s = s.masked_fill(~torch.ones(L, L, dtype=torch.bool).tril(), float("-inf"))
+    return torch.logsumexp(s, dim=-1).transpose(0, 1).numpy()
+
+
 def standalone_check(w, atol=1e-11):
     pr = w.problem
     G = w.n_q_heads // w.n_kv_heads
     scale = 1.0 / math.sqrt(w.head_dim)
     q = w.q.double().numpy(); k = w.k.double().numpy(); v = w.v.double().numpy()
-    O = orc.masked_attention(pr.prompt_len, pr.draft_len, pr.num_segments, pr.segment_len,
-                             pr.boundaries, q, k, v, rope_theta=w.rope_theta)
+    O, LSE = orc.masked_attention(pr.prompt_len, pr.draft_len, pr.num_segments, pr.segment_len,
+                                  pr.boundaries, q, k, v, rope_theta=w.rope_theta, return_lse=True)
     cu = pr.token_offsets()
     worst = 0.0
     for b in range(pr.batch):
         P, T, K, S = pr.prompt_len[b], pr.draft_len[b], pr.num_segments[b], pr.segment_len[b]
-        qb, kb, vb, Ob = (a[cu[b]:cu[b + 1]] for a in (q, k, v, O))
+        qb, kb, vb, Ob, Lb = (a[cu[b]:cu[b + 1]] for a in (q, k, v, O, LSE))
         # prompt + draft alone: appending suffix copies changes nothing for them
         L = P + T
-        ref = library_causal(rope_complex(qb[:L], np.arange(L), w.rope_theta),
-                             rope_complex(kb[:L], np.arange(L), w.rope_theta), vb[:L], G, scale)
+        qr, kr = rope_complex(qb[:L], np.arange(L), w.rope_theta), rope_complex(kb[:L], np.arange(L), w.rope_theta)
+        ref = library_causal(qr, kr, vb[:L], G, scale)
         worst = max(worst, float(np.abs(ref - Ob[:L]).max()))
+        worst = max(worst, float(np.abs(library_causal_lse(qr, kr, G, scale) - Lb[:L]).max()))
         for kk in range(K):
             p = pr.boundaries[b][kk]
             seg = slice(P + T + kk * S, P + T + (kk + 1) * S)
             idx = np.r_[0:P + p, seg]
             L = len(idx)
-            ref = library_causal(rope_complex(qb[idx], np.arange(L), w.rope_theta),
-                                 rope_complex(kb[idx], np.arange(L), w.rope_theta), vb[idx], G, scale)
+            qr, kr = rope_complex(qb[idx], np.arange(L), w.rope_theta), rope_complex(kb[idx], np.arange(L), w.rope_theta)
+            ref = library_causal(qr, kr, vb[idx], G, scale)
             worst = max(worst, float(np.abs(ref[-S:] - Ob[seg]).max()))
+            worst = max(worst, float(np.abs(library_causal_lse(qr, kr, G, scale)[-S:] - Lb[seg]).max()))
     assert worst < atol, worst
     return worst
 
@@ -141,6 +154,32 @@ def test_constant_values_and_lse():
     # all positions zero (theta irrelevant): same as no rotation at position 0 everywhere
     a = orc.attention(q, k, v, orc.dense_mask(4, 12, 3, [5, 12]))
     assert np.allclose(a, O, atol=1e-14)
+
+
+def test_lse_closed_forms_and_scale():
+    # all keys identical: every visible score is the same s, so lse = s + ln(number of visible keys)
+    P, T, S, bounds = 3, 9, 2, [4, 9]
+    N = P + T + 2 * S
+    rng = np.random.default_rng(8)
+    q = rng.normal(size=(N, 2, 8))
+    k = np.tile(rng.normal(size=(1, 1, 8)), (N, 1, 1))
+    v = rng.normal(size=(N, 1, 8))
+    M = orc.dense_mask(P, T, S, bounds)
+    for scale in (None, 0.05, 0.7):
+        sc = (1.0 / math.sqrt(8)) if scale is None else scale
+        O, lse = orc.attention(q, k, v, M, scale=scale, return_lse=True)
+        s = (q * k).sum(-1) * sc                                         # [N, 2]
+        count = M.sum(axis=1).astype(np.float64)                         # visible keys per row
+        assert np.allclose(lse, s + np.log(count)[:, None], rtol=0, atol=1e-13)
+        # identical scores: O is the plain mean of the visible V rows
+        want = (M.astype(np.float64) @ v[:, 0, :]) / count[:, None]
+        assert np.allclose(O[:, 0], want, rtol=0, atol=1e-13) and np.allclose(O[:, 1], want, rtol=0, atol=1e-13)
+    # a non-default scale is the default one applied to queries stretched by the ratio
+    w = wl.make_custom(wl.Problem([4], [12], [2], [3], [[5, 12]]), 2, 1, 64, dtype=torch.float32, seed=9)
+    qq, kk, vv = (x.double().numpy() for x in (w.q, w.k, w.v))
+    a = orc.masked_attention([4], [12], [2], [3], [[5, 12]], qq, kk, vv, scale=0.2, return_lse=True)
+    b = orc.masked_attention([4], [12], [2], [3], [[5, 12]], qq * (0.2 * 8.0), kk, vv, return_lse=True)
+    assert np.allclose(a[0], b[0], rtol=0, atol=1e-13) and np.allclose(a[1], b[1], rtol=0, atol=1e-13)
 
 
 @pytest.mark.parametrize("rows", [[0, 5, 17, 21]])

@@ -15,7 +15,7 @@ import torch
 
 from oracle import pv_oracle as orc
 import pv_workloads as wl
-from tests.test_oracle_attention import library_causal, rope_complex
+from tests.test_oracle_attention import library_causal, library_causal_lse, rope_complex
 
 
 def packed_identities(P, T, S, bounds):
@@ -114,8 +114,9 @@ def standalone_check(w, atol=1e-11):
     G = w.n_q_heads // w.n_kv_heads
     scale = 1.0 / math.sqrt(w.head_dim)
     q = w.q.double().numpy(); k = w.k.double().numpy(); v = w.v.double().numpy()
-    O = orc.masked_attention(pr.prompt_len, pr.draft_len, pr.num_segments, pr.segment_len, pr.boundaries,
-                             q, k, v, rope_theta=w.rope_theta, layout=orc.LAYOUT_INTERLEAVED)
+    O, LSE = orc.masked_attention(pr.prompt_len, pr.draft_len, pr.num_segments, pr.segment_len, pr.boundaries,
+                                  q, k, v, rope_theta=w.rope_theta, layout=orc.LAYOUT_INTERLEAVED,
+                                  return_lse=True)
     cu = pr.token_offsets()
     worst = 0.0
     for b in range(pr.batch):
@@ -123,19 +124,21 @@ def standalone_check(w, atol=1e-11):
         bounds = pr.boundaries[b]
         ids = packed_identities(P, T, S, bounds)
         where = {t: i for i, t in enumerate(ids)}
-        qb, kb, vb, Ob = (a[cu[b]:cu[b + 1]] for a in (q, k, v, O))
+        qb, kb, vb, Ob, Lb = (a[cu[b]:cu[b + 1]] for a in (q, k, v, O, LSE))
         plain = np.array([where[("prefix", i)] for i in range(P)] + [where[("draft", t)] for t in range(T)])
         L = len(plain)
-        ref = library_causal(rope_complex(qb[plain], np.arange(L), w.rope_theta),
-                             rope_complex(kb[plain], np.arange(L), w.rope_theta), vb[plain], G, scale)
+        qr, kr = rope_complex(qb[plain], np.arange(L), w.rope_theta), rope_complex(kb[plain], np.arange(L), w.rope_theta)
+        ref = library_causal(qr, kr, vb[plain], G, scale)
         worst = max(worst, float(np.abs(ref - Ob[plain]).max()))
+        worst = max(worst, float(np.abs(library_causal_lse(qr, kr, G, scale) - Lb[plain]).max()))
         for kk in range(K):
             own = np.array([where[("suffix", kk, a)] for a in range(S)])
             idx = np.r_[plain[:P + bounds[kk]], own]
             L = len(idx)
-            ref = library_causal(rope_complex(qb[idx], np.arange(L), w.rope_theta),
-                                 rope_complex(kb[idx], np.arange(L), w.rope_theta), vb[idx], G, scale)
+            qr, kr = rope_complex(qb[idx], np.arange(L), w.rope_theta), rope_complex(kb[idx], np.arange(L), w.rope_theta)
+            ref = library_causal(qr, kr, vb[idx], G, scale)
             worst = max(worst, float(np.abs(ref[-S:] - Ob[own]).max()))
+            worst = max(worst, float(np.abs(library_causal_lse(qr, kr, G, scale)[-S:] - Lb[own]).max()))
     assert worst < atol, worst
 
 

@@ -180,3 +180,100 @@ def test_judge_logits_against_exact_rational_dot():
         for c in range(2):
             want = sum(Fraction(hidden[r, j]) * Fraction(w2[c, j]) for j in range(24))
             assert Fraction(got[i, c]) == want                           # dyadic inputs: exact in fp64
+
+
+# --- thresholds exactly at equality, and the tie rule of the least confident chunk.  Logits are dyadic,
+# so every margin l_C - l_I is exact in fp64 and can be made to coincide with a threshold to the bit.
+# What happens at equality is written out below from the listing's comparisons, not from the oracle.
+
+def _edge_kwargs(**over):
+    kw = dict(margin_chunk=2.25, margin_chunk_relaxed=1.5, margin_full=6.0, margin_full_relaxed=3.0,
+              margin_short=[3.5, 3.75], rho=0.9, kappa=0, eta=0.0)
+    kw.update(over)
+    return kw
+
+
+def _lg(*margins):
+    """Logit pairs (1 + m, 1) with the given dyadic margins."""
+    return np.array([[1.0 + m, 1.0] for m in margins], dtype=np.float32).reshape(-1, 2)
+
+
+def test_chunk_threshold_at_equality_accepts():
+    # Stage 4 verdict: v_k Correct iff l_C >= l_I and p_2w >= tau_P.  A chunk whose confidence EQUALS
+    # tau_P is Correct; one ulp below is Incorrect.
+    below = float(np.nextafter(np.float32(3.25), np.float32(0)) - np.float32(1.0))   # margin just under 2.25
+    bounds = [[10, 20, 30]]
+    full = _lg(0.0)                                     # weak full verdict: falls through to Stage 6
+    at = orc.decide(_lg(2.25, 2.25, 2.25), full, [3], bounds, **_edge_kwargs())[0]
+    assert list(at[3:6]) == [2, 3, 0]                   # k* = 2, first_reject = K, no Incorrect chunk
+    assert list(at[:3]) == [orc.LABEL_SM_LG, 6, 30]
+    chunk = _lg(2.25, 2.25, 2.25)
+    chunk[1, 0] = np.nextafter(np.float32(3.25), np.float32(0))
+    assert float(chunk[1, 0]) - 1.0 == below < 2.25
+    un = orc.decide(chunk, full, [3], bounds, **_edge_kwargs())[0]
+    assert list(un[3:6]) == [0, 1, 1] and un[2] == 10   # chunk 1 Incorrect: k* = 0, L* = p_0
+    # the plain readout takes the same decision at equality
+    assert list(orc.first_reject(_lg(2.25, 2.25), [2], [[10, 20]], 2.25, 0)[0]) == [2, 1, 20, 0]
+
+
+def test_relaxed_chunk_threshold_is_strict_below():
+    # premature exit counts chunks with p_2w < tau_C^rx: a chunk AT the relaxed threshold is not
+    # counted; Stage 5 needs p_min >= tau_C^rx, which the same chunk satisfies.
+    kw = _edge_kwargs(margin_chunk=0.0, premature=True)
+    three_at = _lg(1.5, 1.5, 1.5, 4.0)
+    r = orc.decide(three_at, None, [4], [[5, 10, 15, 20]], **kw)[0]
+    assert r[8] == 0 and list(r[:2]) == [-1, 0]          # nothing below: keep drafting
+    three_under = _lg(1.25, 1.25, 1.25, 4.0)
+    r = orc.decide(three_under, None, [4], [[5, 10, 15, 20]], **kw)[0]
+    assert r[8] == 3 and r[1] == 1                       # three below: abort
+    # Stage 5 with p_F at tau_F^rx and p_min at tau_C^rx, both exactly: relaxed accept
+    kw5 = _edge_kwargs(margin_chunk=0.0)
+    r = orc.decide(_lg(1.5, 4.0, 4.0), _lg(3.0), [3], [[5, 10, 15]], **kw5)[0]
+    assert list(r[:2]) == [orc.LABEL_SM, 5] and r[8] == 0
+    r = orc.decide(_lg(1.25, 4.0, 4.0), _lg(3.0), [3], [[5, 10, 15]], **kw5)[0]
+    assert list(r[:2]) == [orc.LABEL_SM_LG, 6] and r[8] == 1
+
+
+def test_full_thresholds_at_equality():
+    chunk = _lg(4.0, -1.0, 4.0, 4.0)                     # K = 4 > K^sd = 2; chunk 1 Incorrect and below relaxed
+    bounds = [[5, 10, 15, 20]]
+    # Stage 2: p_F >= tau_F accepts at equality
+    assert list(orc.decide(chunk, _lg(6.0), [4], bounds, **_edge_kwargs())[0][:2]) == [orc.LABEL_SM, 2]
+    assert orc.decide(chunk, _lg(6.0), [4], bounds, **_edge_kwargs())[0][9] == 1
+    r = orc.decide(chunk, _lg(5.75), [4], bounds, **_edge_kwargs())[0]
+    assert list(r[:3]) == [orc.LABEL_SM_LG, 6, 5] and r[9] == 0
+    # Stage 5: p_F >= tau_F^rx at equality (every chunk above the relaxed chunk threshold)
+    good = _lg(4.0, 4.0, 4.0, 4.0)
+    assert list(orc.decide(good, _lg(3.0), [4], bounds, **_edge_kwargs())[0][:2]) == [orc.LABEL_SM, 5]
+    assert list(orc.decide(good, _lg(2.75), [4], bounds, **_edge_kwargs())[0][:3]) == [orc.LABEL_SM_LG, 6, 20]
+    # Stage 3: K <= K^sd and p_F >= tau_sd^(K) at equality, per chunk count
+    bad2, bad1 = _lg(-1.0, -1.0), _lg(-1.0)
+    assert list(orc.decide(bad2, _lg(3.75), [2], [[5, 9]], **_edge_kwargs())[0][:2]) == [orc.LABEL_SM, 3]
+    assert list(orc.decide(bad2, _lg(3.5), [2], [[5, 9]], **_edge_kwargs())[0][:3]) == [orc.LABEL_LG, 6, 0]
+    assert list(orc.decide(bad1, _lg(3.5), [1], [[5]], **_edge_kwargs())[0][:2]) == [orc.LABEL_SM, 3]
+    assert list(orc.decide(bad1, _lg(3.25), [1], [[5]], **_edge_kwargs())[0][:3]) == [orc.LABEL_LG, 6, 0]
+    # K = K^sd + 1 never takes Stage 3
+    assert orc.decide(_lg(-1.0, -1.0, -1.0), _lg(3.75), [3], [[5, 9, 12]], **_edge_kwargs())[0][1] == 6
+
+
+def test_least_confident_chunk_first_of_equals():
+    # output [10]: index of the least confident chunk; of several equal minima the first
+    r = orc.decide(_lg(4.0, 0.5, 3.0, 0.5, 0.5), _lg(0.0), [5], [[1, 2, 3, 4, 5]], **_edge_kwargs())[0]
+    assert r[10] == 1
+    r = orc.decide(_lg(0.5, 0.5), _lg(0.0), [2], [[1, 2]], **_edge_kwargs())[0]
+    assert r[10] == 0
+    r = orc.decide(_lg(4.0, 3.0, -2.0), _lg(0.0), [3], [[1, 2, 3]], **_edge_kwargs())[0]
+    assert r[10] == 2
+    assert orc.decide(_lg(), _lg(0.0), [0], [[]], **_edge_kwargs())[0][10] == -1
+
+
+def test_short_draft_thresholds_are_the_listed_taus():
+    # tau_sd^(K) = min(tau_sd + 0.02 (K - 1), tau_F^rx): with tau_sd = 0.90 and tau_F^rx = 0.95 the
+    # thresholds for K = 1..4 are 0.90, 0.92, 0.94, 0.95 (typed here, not computed); the margin of
+    # each must have exactly that two-way confidence (60-digit logistic function).
+    getcontext().prec = 60
+    for m, tau in zip(orc.short_draft_margins(0.90, 0.95, 4), ("0.90", "0.92", "0.94", "0.95")):
+        conf = 1 / (1 + (-Decimal(m)).exp())
+        assert abs(conf - Decimal(tau)) < Decimal("1e-15"), (m, tau)
+    for m, tau in zip(orc.short_draft_margins(0.95, 0.95, 2), ("0.95", "0.95")):
+        assert abs(1 / (1 + (-Decimal(m)).exp()) - Decimal(tau)) < Decimal("1e-15")
