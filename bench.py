@@ -42,10 +42,10 @@ def unmasked_pairs(problem) -> int:
 
 
 def ensure_built() -> None:
-    lib = os.path.join(ROOT, "paper_2605_04263_amd", "libpv.so")
-    if not os.path.exists(lib):
-        from paper_2605_04263_amd.build import build_library
-        build_library(verbose=False)
+    """Loads what is built; compiles only if there is no library or a source is newer than it."""
+    from paper_2605_04263_amd import build
+    if build.library_is_stale():
+        build.build_library(verbose=False)
 
 
 def cpu_baseline(w, eff_flops: float) -> dict:

@@ -150,6 +150,11 @@ pv_status pv_segment_attention(const pv_sizes* sizes, const void* plan_dev, cons
                                int32_t out_dtype, float softmax_scale, float rope_theta,
                                void* workspace, int64_t workspace_bytes, void* stream);
 
+/* Host only.  The logit margin at which the two-way confidence p_2w = e^{l_C} / (e^{l_C} + e^{l_I})
+ * of appendix "Notation and judge calibration" equals tau: ln(tau / (1 - tau)), the form in which
+ * every threshold of pv_first_reject and pv_policy is given.  0 < tau < 1, else PV_ERR_SHAPE. */
+pv_status pv_margin_from_tau(double tau, double* margin_out);
+
 /* Readout.  Verdict of segment k is Correct iff l_C >= l_I and l_C - l_I >= margin_threshold
  * (margin_threshold = ln(tau / (1 - tau)) makes this the two-way-confidence rule p_2w >= tau),
  * compared in fp64.  Per request writes int32 (first_reject, k_star, L_star, n_incorrect):
@@ -232,7 +237,8 @@ pv_status pv_plan_export(const pv_sizes* sizes, const void* plan_dev, int32_t* p
  *                        (PV_ERR_SHAPE if nothing was recorded).
  *   pv_profile_read_all  waits for and returns the durations of the calls since enabling, oldest
  *                        first: the last min(calls, PV_PROFILE_RING, capacity) of them into
- *                        ms_host (host memory), their number into *n_out. */
+ *                        ms_host (host memory), their number into *n_out.
+ * Disabling destroys the events (read the durations first); the three calls serialise on a lock. */
 enum { PV_PROFILE_RING = 1024 };
 pv_status pv_profile_enable(int32_t on);
 pv_status pv_profile_read(float* main_kernel_ms);

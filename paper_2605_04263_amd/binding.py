@@ -7,7 +7,6 @@ library is missing, importing this module fails.
 from __future__ import annotations
 
 import ctypes as C
-import math
 import os
 from dataclasses import dataclass
 from typing import Optional, Sequence
@@ -78,13 +77,14 @@ def _load() -> C.CDLL:
                                     C.c_void_p, C.c_void_p]
     lib.pv_decide.argtypes = [P(PvSizes), C.c_void_p, C.c_void_p, C.c_void_p, P(PvPolicy),
                               C.c_void_p, C.c_void_p]
+    lib.pv_margin_from_tau.argtypes = [C.c_double, P(C.c_double)]
     lib.pv_profile_enable.argtypes = [C.c_int32]
     lib.pv_profile_read.argtypes = [P(C.c_float)]
     lib.pv_profile_read_all.argtypes = [P(C.c_float), C.c_int32, P(C.c_int32)]
     for name in ("pv_query_sizes", "pv_build_mask", "pv_masked_attention", "pv_segment_attention", "pv_first_reject",
                  "pv_plan_export", "pv_profile_enable", "pv_profile_read", "pv_profile_read_all",
                  "pv_last_hip_error",
-                 "pv_judge_logits", "pv_decide"):
+                 "pv_judge_logits", "pv_decide", "pv_margin_from_tau"):
         getattr(lib, name).restype = C.c_int32
     lib.pv_strerror.argtypes = [C.c_int32]
     lib.pv_strerror.restype = C.c_char_p
@@ -281,9 +281,14 @@ def pv_profile_read_all() -> list:
     return [buf[i] for i in range(n.value)]
 
 
-def margin_from_tau(tau: float) -> float:
-    """ln(tau / (1 - tau)): the margin at which the two-way confidence equals tau."""
-    return math.log(tau / (1.0 - tau))
+def pv_margin_from_tau(tau: float) -> float:
+    """The logit margin at which the two-way confidence equals tau (computed by the library)."""
+    out = C.c_double(0.0)
+    _check(lib.pv_margin_from_tau(tau, C.byref(out)), "pv_margin_from_tau")
+    return out.value
+
+
+margin_from_tau = pv_margin_from_tau
 
 
 class Verifier:

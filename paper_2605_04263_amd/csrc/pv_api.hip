@@ -2,6 +2,8 @@
 // stream.  Nothing here allocates device memory or synchronises (pv_profile_read excepted).
 #include <cmath>
 #include <cstring>
+#include <mutex>
+#include <new>
 #include <vector>
 
 #include "pv_internal.h"
@@ -9,8 +11,10 @@
 namespace pv {
 
 static thread_local int32_t g_last_hip = 0;
+// Profiling state, all of it under g_profile_lock.
+static std::mutex g_profile_lock;
 static bool g_profile = false;
-static hipEvent_t g_ev[PV_PROFILE_RING][2];     // created on first use, kept until the process ends
+static hipEvent_t g_ev[PV_PROFILE_RING][2];     // created on first use, destroyed when profiling is switched off
 static int64_t g_ev_calls = 0;                  // calls recorded since profiling was enabled
 
 static inline pv_status hip_fail(hipError_t e) {
@@ -272,7 +276,12 @@ pv_status pv_build_mask(const pv_problem* problem, const pv_sizes* sizes, void* 
   if (misaligned(plan_dev)) return PV_ERR_ALIGN;
 
   // Host image of the uploaded part of the plan: header, per-request arrays, boundaries.
-  std::vector<int32_t> img((size_t)h.off_device_begin, 0);
+  std::vector<int32_t> img;
+  try {
+    img.assign((size_t)h.off_device_begin, 0);
+  } catch (const std::bad_alloc&) {               // no exception may cross the C boundary
+    return PV_ERR_WORKSPACE;
+  }
   std::memcpy(img.data(), &h, sizeof(h));
   const int B = problem->batch;
   int64_t tok = 0, seg = 0, qt = 0, kp = 0, mk = 0, ns = 0, sgt = 0, qd = 0;
@@ -363,20 +372,26 @@ static pv_status attention_call(const pv_sizes* sizes, const void* plan_dev, con
                         (char*)workspace, wl, s);
   } else {
     hipEvent_t ev0 = nullptr, ev1 = nullptr;
-    if (g_profile) {
+    std::unique_lock<std::mutex> guard(g_profile_lock);
+    const bool profiling = g_profile;
+    if (profiling) {
       hipEvent_t* pair = g_ev[g_ev_calls % PV_PROFILE_RING];
-      if (!pair[1]) {
+      if (!pair[0]) {
         e = hipEventCreate(&pair[0]);
-        if (e != hipSuccess) return hip_fail(e);
+        if (e != hipSuccess) { pair[0] = nullptr; return hip_fail(e); }
+      }
+      if (!pair[1]) {
         e = hipEventCreate(&pair[1]);
-        if (e != hipSuccess) return hip_fail(e);
+        if (e != hipSuccess) { pair[1] = nullptr; return hip_fail(e); }
       }
       ev0 = pair[0];
       ev1 = pair[1];
+    } else {
+      guard.unlock();                               // the ordinary path holds no lock while launching
     }
     e = launch_attn_bf16((const int32_t*)plan_dev, h, q, k, v, out, lse, hq, hkv, d, out_dtype,
                          scale, freq, rope, (char*)workspace, wl, segments_only, ev0, ev1, s);
-    if (e == hipSuccess && g_profile) ++g_ev_calls;
+    if (e == hipSuccess && profiling) ++g_ev_calls;
   }
   if (e != hipSuccess) return hip_fail(e);
   return PV_OK;
@@ -483,9 +498,20 @@ pv_status pv_plan_export(const pv_sizes* sizes, const void* plan_dev, int32_t* p
 }
 
 pv_status pv_profile_enable(int32_t on) {
+  std::lock_guard<std::mutex> guard(g_profile_lock);
   g_profile = on != 0;
   g_ev_calls = 0;
-  return PV_OK;
+  hipError_t first = hipSuccess;
+  if (!g_profile) {                                 // switched off: give the events back
+    for (auto& pair : g_ev)
+      for (hipEvent_t& ev : pair)
+        if (ev) {
+          const hipError_t e = hipEventDestroy(ev);
+          if (e != hipSuccess && first == hipSuccess) first = e;
+          ev = nullptr;
+        }
+  }
+  return first == hipSuccess ? PV_OK : hip_fail(first);
 }
 
 static pv_status profile_pair_ms(int64_t call, float* ms) {
@@ -499,6 +525,7 @@ static pv_status profile_pair_ms(int64_t call, float* ms) {
 
 pv_status pv_profile_read(float* main_kernel_ms) {
   if (!main_kernel_ms) return PV_ERR_NULL;
+  std::lock_guard<std::mutex> guard(g_profile_lock);
   if (!g_profile || g_ev_calls == 0) return PV_ERR_SHAPE;
   return profile_pair_ms(g_ev_calls - 1, main_kernel_ms);
 }
@@ -507,6 +534,7 @@ pv_status pv_profile_read_all(float* ms_host, int32_t capacity, int32_t* n_out) 
   if (!ms_host || !n_out) return PV_ERR_NULL;
   if (capacity < 0) return PV_ERR_SHAPE;
   *n_out = 0;
+  std::lock_guard<std::mutex> guard(g_profile_lock);
   if (!g_profile) return PV_ERR_SHAPE;
   int64_t n = g_ev_calls < PV_PROFILE_RING ? g_ev_calls : PV_PROFILE_RING;
   if (n > capacity) n = capacity;
@@ -515,6 +543,13 @@ pv_status pv_profile_read_all(float* ms_host, int32_t capacity, int32_t* n_out) 
     if (st != PV_OK) return st;
   }
   *n_out = (int32_t)n;
+  return PV_OK;
+}
+
+pv_status pv_margin_from_tau(double tau, double* margin_out) {
+  if (!margin_out) return PV_ERR_NULL;
+  if (!(tau > 0.0 && tau < 1.0)) return PV_ERR_SHAPE;
+  *margin_out = std::log(tau / (1.0 - tau));
   return PV_OK;
 }
 

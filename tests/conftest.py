@@ -8,8 +8,8 @@ if ROOT not in sys.path:
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
-    # Tests load the library that is already built; compile only if there is none.
-    lib = os.path.join(ROOT, "paper_2605_04263_amd", "libpv.so")
-    if not os.path.exists(lib):
-        from paper_2605_04263_amd.build import build_library
-        build_library(verbose=False)
+    # Tests load the library that is already built; compile only if there is none, or if a source
+    # is newer than it (a stale binary would be tested against the wrong code).
+    from paper_2605_04263_amd import build
+    if build.library_is_stale():
+        build.build_library(verbose=False)

@@ -18,7 +18,7 @@ def make_verifier(pv, w, dense_mask=False):
                        dense_mask=dense_mask, layout=pr.layout)
 
 
-def run_gpu_attention(pv, w, out_dtype=None, lse=False, ver=None):
+def run_gpu_attention(pv, w, out_dtype=None, lse=False, ver=None, softmax_scale=0.0):
     if ver is None:
         ver = make_verifier(pv, w)
         ver.build_mask()
@@ -26,16 +26,16 @@ def run_gpu_attention(pv, w, out_dtype=None, lse=False, ver=None):
     q, k, v = w.q.to(dev), w.k.to(dev), w.v.to(dev)
     out = torch.empty(q.shape, dtype=out_dtype or w.dtype, device=dev)
     l = torch.empty(w.n_q_heads, w.problem.total_tokens, dtype=torch.float32, device=dev) if lse else None
-    ver.attention(q, k, v, out=out, lse=l, rope_theta=w.rope_theta)
+    ver.attention(q, k, v, out=out, lse=l, rope_theta=w.rope_theta, softmax_scale=softmax_scale)
     torch.cuda.synchronize()
     return (out, l) if lse else out
 
 
-def oracle_attention(w, rows_per_request=None, return_lse=False):
+def oracle_attention(w, rows_per_request=None, return_lse=False, scale=None):
     pr = w.problem
     return orc.masked_attention(pr.prompt_len, pr.draft_len, pr.num_segments, pr.segment_len,
                                 pr.boundaries, w.q.double().numpy(), w.k.double().numpy(),
-                                w.v.double().numpy(), rope_theta=w.rope_theta,
+                                w.v.double().numpy(), rope_theta=w.rope_theta, scale=scale,
                                 rows_per_request=rows_per_request, return_lse=return_lse, layout=pr.layout)
 
 

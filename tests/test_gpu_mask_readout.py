@@ -80,6 +80,52 @@ def test_readout_named_and_patterns():
                 assert np.array_equal(got, exp), (name, tau, mode)
 
 
+def test_70b_plan_mask_work_list_readout():
+    # the long configuration (4 requests of 14 336 tokens, 1 792 tiles: the plan comes from the separate
+    # upload / tokens / tiles / ranking kernels): positions and judge rows of every token, the dense
+    # mask of every request entry by entry (822 MB on the device, one request at a time on the host),
+    # the row descriptors (rebuilt into mask rows), the tile classifier and the order of the work
+    # list against the oracle's mask, and the readout in both modes
+    w = wl.make("70b")
+    pr = w.problem
+    ver = gc.make_verifier(pv, w, dense_mask=True)
+    ver.build_mask()
+    pos, ae, bs, jr = pv.pv_plan_export(ver.sizes, ver.plan)
+    torch.cuda.synchronize()
+    assert ver.sizes.total_tokens == pr.total_tokens == 57344 and ver.sizes.total_segments == 256
+    opos, ojr = gc.oracle_plan_arrays(pr)
+    assert np.array_equal(pos.cpu().numpy().astype(np.int64), opos)
+    assert np.array_equal(jr.cpu().numpy().astype(np.int64), ojr)
+    tiles, work = _work_list(ver)
+    ae_h, bs_h = ae.cpu().numpy(), bs.cpu().numpy()
+    cu = pr.token_offsets()
+    off, t = 0, 0
+    for b in range(pr.batch):
+        n = pr.seq_len(b)
+        print(f"70b request {b}: oracle mask", flush=True)
+        M = orc.dense_mask(pr.prompt_len[b], pr.draft_len[b], pr.segment_len[b], pr.boundaries[b])
+        got = ver.dense_mask[off:off + n * n].cpu().numpy().reshape(n, n)
+        assert np.array_equal(got, M), b
+        del got
+        # key j is visible to row i iff j < a_end or b_start <= j <= i: sampled rows of the request
+        j = np.arange(n)
+        for i in gc.sample_rows(pr, n_random=64, seed=b)[b]:
+            a, s0 = int(ae_h[cu[b] + i]), int(bs_h[cu[b] + i])
+            assert np.array_equal(((j < a) | ((j >= s0) & (j <= i))).astype(np.uint8), M[i]), (b, i)
+        t = check_tiles_of_request(tiles, t, cu[b], M)
+        del M
+        off += n * n
+    assert t == len(tiles) == 1792
+    check_work_order(tiles, work)
+    lg = w.logits.to(ver.device)
+    for tau in (0.5, 0.88, 0.985, 0.998):
+        thr = orc.margin_threshold(tau)
+        for mode in (0, 1):
+            got = ver.first_reject(lg, thr, mode).cpu().numpy()
+            exp = orc.first_reject(w.logits.numpy(), pr.num_segments, pr.boundaries, thr, mode)
+            assert np.array_equal(got, exp), (tau, mode)
+
+
 def test_readout_all_patterns_k6_batched():
     K = 6
     pats = list(itertools.product([0, 1], repeat=K))
@@ -125,10 +171,41 @@ def _work_list(ver):
     return tiles, work
 
 
+def check_tiles_of_request(tiles, t, tok_base_want, M):
+    """Tile classifier of one request against its dense mask M (oracle): every visible (row, key)
+    pair lies in a listed key tile, tiles listed as fully visible are, listed tiles hold a visible
+    pair.  `t` is the index of the request's first tile; returns the index after its last."""
+    n = M.shape[0]
+    nkt = (n + 63) // 64
+    Mp = np.zeros((n, nkt * 64), dtype=np.uint8)
+    Mp[:, :n] = M
+    for t0 in range(0, n, 32):
+        tok_base, tt0, rows, n_full, n_a, jb0, jb1, _ = (int(x) for x in tiles[t])
+        assert (tok_base, tt0, rows) == (tok_base_want, t0, min(32, n - t0))
+        blk = Mp[t0:t0 + rows].reshape(rows, nkt, 64)
+        any_vis = blk.any(axis=(0, 2))
+        all_vis = blk.all(axis=(0, 2))
+        listed = np.zeros(nkt, dtype=bool)
+        listed[:n_a] = True
+        listed[jb0:jb1] = True
+        assert 0 <= n_full <= n_a <= jb0 <= jb1 <= nkt
+        assert not (any_vis & ~listed).any(), t0                 # nothing visible is skipped
+        assert all_vis[:n_full].all(), t0                        # unmasked tiles really are
+        # the classifier is tight: listed tiles hold a visible pair
+        assert any_vis[listed].all(), t0
+        t += 1
+    return t
+
+
+def check_work_order(tiles, work):
+    cost = tiles[:, 4] + (tiles[:, 6] - tiles[:, 5])
+    order = np.argsort(-cost, kind="stable")
+    assert np.array_equal(work, tiles[order])
+
+
 def check_work_list(pr):
-    """Tile classifier against the oracle's dense mask: every visible (row, key) pair lies in a listed
-    key tile, tiles listed as fully visible are, and the work list is the tile list sorted longest
-    first (stable)."""
+    """Tile classifier against the oracle's dense mask, and the work list = the tile list sorted
+    longest first (stable)."""
     w = wl.make_custom(pr, 4, 2, 64, dtype=torch.float32, seed=1)
     ver = gc.make_verifier(pv, w)
     ver.build_mask()
@@ -137,31 +214,10 @@ def check_work_list(pr):
     cu = pr.token_offsets()
     t = 0
     for b in range(pr.batch):
-        n = pr.seq_len(b)
         M = orc.dense_mask(pr.prompt_len[b], pr.draft_len[b], pr.segment_len[b], pr.boundaries[b])
-        nkt = (n + 63) // 64
-        Mp = np.zeros((n, nkt * 64), dtype=np.uint8)
-        Mp[:, :n] = M
-        for t0 in range(0, n, 32):
-            tok_base, tt0, rows, n_full, n_a, jb0, jb1, _ = (int(x) for x in tiles[t])
-            assert (tok_base, tt0, rows) == (cu[b], t0, min(32, n - t0))
-            blk = Mp[t0:t0 + rows].reshape(rows, nkt, 64)
-            any_vis = blk.any(axis=(0, 2))
-            all_vis = blk.all(axis=(0, 2))
-            listed = np.zeros(nkt, dtype=bool)
-            listed[:n_a] = True
-            listed[jb0:jb1] = True
-            assert 0 <= n_full <= n_a <= jb0 <= jb1 <= nkt
-            assert not (any_vis & ~listed).any(), (b, t0)            # nothing visible is skipped
-            assert all_vis[:n_full].all(), (b, t0)                   # unmasked tiles really are
-            # the classifier is tight: listed tiles hold a visible pair, except inside the gap-free
-            # ranges it is allowed to over-cover (none for these layouts)
-            assert any_vis[listed].all(), (b, t0)
-            t += 1
+        t = check_tiles_of_request(tiles, t, cu[b], M)
     assert t == len(tiles)
-    cost = tiles[:, 4] + (tiles[:, 6] - tiles[:, 5])
-    order = np.argsort(-cost, kind="stable")
-    assert np.array_equal(work, tiles[order])
+    check_work_order(tiles, work)
 
 
 @pytest.mark.parametrize("idx", range(len(EDGE_PROBLEMS)))

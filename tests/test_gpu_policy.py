@@ -74,11 +74,48 @@ def test_decide_ragged_random_and_named():
     chunk = np.stack([rng.normal(3, 4, n), rng.normal(0, 1, n)], axis=1).astype(np.float32)
     full = np.stack([rng.normal(3, 3, B), rng.normal(0, 1, B)], axis=1).astype(np.float32)
     check_decide(pr, chunk, full)
-    for name in ("tiny", "8b", "ragged"):
+    for name in ("tiny", "8b", "ragged", "14b", "70b"):
         w = wl.make(name)
         prn = w.problem
         full = np.stack([rng.normal(3, 3, prn.batch), rng.normal(0, 1, prn.batch)], axis=1).astype(np.float32)
         check_decide(prn, w.logits.numpy(), full)
+
+
+def test_decide_thresholds_at_exact_equality():
+    # dyadic logits: the fp64 margin l_C - l_I coincides with a threshold to the bit.  At equality a
+    # chunk is Correct (>= tau_P), is not counted as below the relaxed chunk threshold (< tau_C^rx), and
+    # the full-answer confidence passes the strict, short-draft and relaxed gates (>=); one float below,
+    # none of that holds.  Expected values from the oracle, whose equality cases are pinned on the CPU.
+    def lg(*margins):
+        return np.array([[1.0 + m, 1.0] for m in margins], dtype=np.float32).reshape(-1, 2)
+    under = float(np.nextafter(np.float32(3.25), np.float32(0))) - 1.0          # just below 2.25
+    cases = [  # (chunk margins, full margin)
+        ((2.25, 2.25, 2.25), 0.0), ((2.25, under, 2.25), 0.0), ((1.5, 1.5, 1.5, 4.0), 0.0),
+        ((1.25, 1.25, 1.25, 4.0), 0.0), ((1.5, 4.0, 4.0), 3.0), ((1.25, 4.0, 4.0), 3.0),
+        ((4.0, -1.0, 4.0, 4.0), 6.0), ((4.0, -1.0, 4.0, 4.0), 5.75), ((4.0, 4.0, 4.0, 4.0), 3.0),
+        ((4.0, 4.0, 4.0, 4.0), 2.75), ((-1.0, -1.0), 3.75), ((-1.0, -1.0), 3.5), ((-1.0,), 3.5), ((-1.0,), 3.25),
+        ((4.0, 0.5, 3.0, 0.5, 0.5), 0.0), ((0.5, 0.5), 0.0), ((), 0.0),
+    ]
+    K = [len(c[0]) for c in cases]
+    pr = wl.Problem([2] * len(cases), [40] * len(cases), K, [1] * len(cases),
+                    [[5 * (k + 1) for k in range(n)] for n in K])
+    chunk = np.concatenate([lg(*c[0]) for c in cases])
+    chunk[4, 0] = np.nextafter(np.float32(3.25), np.float32(0))                 # the `under` entry, exactly
+    full = np.concatenate([lg(c[1]) for c in cases])
+    ver = verifier_for(pr)
+    for premature in (False, True):
+        for margin_chunk in (2.25, 0.0):
+            kw = dict(margin_chunk=margin_chunk, margin_chunk_relaxed=1.5, margin_full=6.0, margin_full_relaxed=3.0,
+                      margin_short=[3.5, 3.75], rho=0.9, kappa=0, eta=0.0, premature=premature)
+            pol = pv.make_policy(margin_chunk, 1.5, 6.0, 3.0, [3.5, 3.75], 0.9, 0, 0.0, 3, premature)
+            got = ver.decide(torch.from_numpy(chunk).to(ver.device),
+                             None if premature else torch.from_numpy(full).to(ver.device), pol).cpu().numpy()
+            exp = orc.decide(chunk, None if premature else full, pr.num_segments, pr.boundaries, **kw)
+            assert np.array_equal(got, exp), (premature, margin_chunk, got, exp)
+    # and the plain readout at the same equality
+    got = ver.first_reject(torch.from_numpy(chunk).to(ver.device), 2.25, 0).cpu().numpy()
+    assert np.array_equal(got, orc.first_reject(chunk, pr.num_segments, pr.boundaries, 2.25, 0))
+    assert got[0].tolist() == [3, 2, 15, 0] and got[1].tolist() == [1, 0, 5, 1]
 
 
 def test_decide_agrees_with_first_reject():
