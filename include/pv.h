@@ -150,6 +150,31 @@ pv_status pv_segment_attention(const pv_sizes* sizes, const void* plan_dev, cons
                                int32_t out_dtype, float softmax_scale, float rope_theta,
                                void* workspace, int64_t workspace_bytes, void* stream);
 
+/* pv_masked_attention for callers that cannot allocate device memory or keep a workspace of their
+ * own (code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): the
+ * workspace is a fixed array inside the library's device image, PV_STATIC_WORKSPACE_BYTES per GPU,
+ * held from the first use on that GPU until the process ends.  No workspace arguments; everything
+ * else as for pv_masked_attention, and the result is bit-identical to it.  The call allocates
+ * nothing and frees nothing.
+ *   Limit      the bytes this call needs (rotary table, rotated K, transposed V: about
+ *              2 * Hkv * D * 2 + 4 * D bytes per token; pv_static_workspace_needed reports them;
+ *              the partial results of pv_segment_attention are not part of it) must not exceed
+ *              PV_STATIC_WORKSPACE_BYTES, else PV_ERR_WORKSPACE and nothing is launched.  The
+ *              8B-like configuration of 3 072 tokens needs 14.2 MB.
+ *   Sharing    every call on a GPU uses that GPU's one array: calls that may overlap on one GPU
+ *              (different streams, different threads) race and must be serialised by the caller.
+ *              Nothing in the array has to survive between calls or start at zero: each call
+ *              rewrites every byte it later reads, padding included.
+ *   First use  the first call on a device looks the array's address up once (a host-side query,
+ *              no launch); make that call outside graph capture. */
+enum { PV_STATIC_WORKSPACE_BYTES = 32 << 20 };
+pv_status pv_masked_attention_static(const pv_sizes* sizes, const void* plan_dev, const void* q,
+                                     const void* k, const void* v, void* out, float* lse,
+                                     int32_t out_dtype, float softmax_scale, float rope_theta,
+                                     void* stream);
+/* Host only: workspace bytes pv_masked_attention_static would use for `sizes`. */
+pv_status pv_static_workspace_needed(const pv_sizes* sizes, int64_t* bytes_out);
+
 /* Host only.  The logit margin at which the two-way confidence p_2w = e^{l_C} / (e^{l_C} + e^{l_I})
  * of appendix "Notation and judge calibration" equals tau: ln(tau / (1 - tau)), the form in which
  * every threshold of pv_first_reject and pv_policy is given.  0 < tau < 1, else PV_ERR_SHAPE. */

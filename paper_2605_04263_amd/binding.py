@@ -69,6 +69,10 @@ def _load() -> C.CDLL:
                                         C.c_void_p, C.c_void_p, C.c_int32, C.c_float, C.c_float,
                                         C.c_void_p, C.c_int64, C.c_void_p]
     lib.pv_segment_attention.argtypes = lib.pv_masked_attention.argtypes
+    lib.pv_masked_attention_static.argtypes = [P(PvSizes), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                               C.c_void_p, C.c_void_p, C.c_int32, C.c_float, C.c_float,
+                                               C.c_void_p]
+    lib.pv_static_workspace_needed.argtypes = [P(PvSizes), P(C.c_int64)]
     lib.pv_first_reject.argtypes = [P(PvSizes), C.c_void_p, C.c_void_p, C.c_double, C.c_int32,
                                     C.c_void_p, C.c_void_p]
     lib.pv_plan_export.argtypes = [P(PvSizes), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
@@ -84,7 +88,8 @@ def _load() -> C.CDLL:
     for name in ("pv_query_sizes", "pv_build_mask", "pv_masked_attention", "pv_segment_attention", "pv_first_reject",
                  "pv_plan_export", "pv_profile_enable", "pv_profile_read", "pv_profile_read_all",
                  "pv_last_hip_error",
-                 "pv_judge_logits", "pv_decide", "pv_margin_from_tau"):
+                 "pv_judge_logits", "pv_decide", "pv_margin_from_tau", "pv_masked_attention_static",
+                 "pv_static_workspace_needed"):
         getattr(lib, name).restype = C.c_int32
     lib.pv_strerror.argtypes = [C.c_int32]
     lib.pv_strerror.restype = C.c_char_p
@@ -185,6 +190,25 @@ def pv_masked_attention(sizes: PvSizes, plan: torch.Tensor, q: torch.Tensor, k: 
               softmax_scale, rope_theta, _ptr(workspace), workspace.numel() * workspace.element_size(),
               _stream()),
            "pv_segment_attention" if segments_only else "pv_masked_attention")
+
+
+PV_STATIC_WORKSPACE_BYTES = 32 << 20
+
+
+def pv_static_workspace_needed(sizes: PvSizes) -> int:
+    out = C.c_int64(0)
+    _check(lib.pv_static_workspace_needed(C.byref(sizes), C.byref(out)), "pv_static_workspace_needed")
+    return out.value
+
+
+def pv_masked_attention_static(sizes: PvSizes, plan: torch.Tensor, q: torch.Tensor, k: torch.Tensor,
+                               v: torch.Tensor, out: torch.Tensor, lse: Optional[torch.Tensor] = None,
+                               softmax_scale: float = 0.0, rope_theta: float = 0.0) -> None:
+    """pv_masked_attention with the library's own fixed workspace (no workspace argument)."""
+    out_dtype = PV_F32 if out.dtype == torch.float32 else PV_BF16
+    _check(lib.pv_masked_attention_static(C.byref(sizes), _ptr(plan), _ptr(q), _ptr(k), _ptr(v), _ptr(out),
+                                          _ptr(lse), out_dtype, softmax_scale, rope_theta, _stream()),
+           "pv_masked_attention_static")
 
 
 def pv_segment_attention(sizes: PvSizes, plan: torch.Tensor, q: torch.Tensor, k: torch.Tensor,

@@ -17,6 +17,14 @@ static bool g_profile = false;
 static hipEvent_t g_ev[PV_PROFILE_RING][2];     // created on first use, destroyed when profiling is switched off
 static int64_t g_ev_calls = 0;                  // calls recorded since profiling was enabled
 
+// Workspace of pv_masked_attention_static: part of the library's device image, one copy per GPU at an
+// address of its own.  In host code this name is only a handle for hipGetSymbolAddress; the address
+// looked up there (per device) is what kernels and host calls are given.
+static __device__ __align__(256) unsigned char scratch[PV_STATIC_WORKSPACE_BYTES];
+constexpr int kMaxDevices = 64;
+static std::mutex g_scratch_lock;
+static void* g_scratch_ptr[kMaxDevices];        // per device, filled on first use with that device current
+
 static inline pv_status hip_fail(hipError_t e) {
   g_last_hip = (int32_t)e;
   return PV_ERR_HIP;
@@ -92,10 +100,12 @@ AttnWorkspace attn_workspace_layout(int64_t total_tokens, int64_t padded_keys, i
     o = align_up(o + (int64_t)hkv * padded_keys * d * 2, 256);
     w.split = segment_split(n_seg_tiles, hkv);
     w.off_part = o;
+    w.total_full = o;
     if (w.split > 1) o = align_up(o + n_seg_tiles * hq * w.split * 32 * (d + 2) * 4, 256);
   } else {
     o = align_up(o + total_tokens * hkv * d * 4, 256);
     w.off_vt = o;
+    w.total_full = o;
   }
   w.total = o;
   return w;
@@ -336,7 +346,7 @@ static pv_status attention_call(const pv_sizes* sizes, const void* plan_dev, con
                                 const void* k, const void* v, void* out, float* lse,
                                 int32_t out_dtype, float softmax_scale, float rope_theta,
                                 void* workspace, int64_t workspace_bytes, void* stream,
-                                bool segments_only) {
+                                bool segments_only, bool library_workspace = false) {
   PlanHeader h;
   pv_status st = check_sizes(sizes, &h);
   if (st != PV_OK) return st;
@@ -350,7 +360,9 @@ static pv_status attention_call(const pv_sizes* sizes, const void* plan_dev, con
   const AttnWorkspace wl =
       attn_workspace_layout(sizes->total_tokens, sizes->padded_keys, sizes->n_seg_tiles, hq, hkv, d,
                             sizes->in_dtype);
-  if (workspace_bytes < wl.total) return PV_ERR_WORKSPACE;
+  // a caller's workspace must have the size pv_query_sizes reports (which also covers the
+  // segment-only call); the library's own fixed array only has to hold what the whole pass uses
+  if (workspace_bytes < (library_workspace ? wl.total_full : wl.total)) return PV_ERR_WORKSPACE;
   if (misaligned(plan_dev) || misaligned(q) || misaligned(k) || misaligned(v) ||
       misaligned(out) || misaligned(workspace) || ((uintptr_t)lse & 3u))
     return PV_ERR_ALIGN;
@@ -403,6 +415,57 @@ pv_status pv_masked_attention(const pv_sizes* sizes, const void* plan_dev, const
                               void* workspace, int64_t workspace_bytes, void* stream) {
   return attention_call(sizes, plan_dev, q, k, v, out, lse, out_dtype, softmax_scale, rope_theta,
                         workspace, workspace_bytes, stream, false);
+}
+
+// Address of this device's copy of `scratch` (looked up once per device, with that device current).
+static pv_status static_workspace(void** ptr) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return hip_fail(e);
+  if (dev < 0 || dev >= kMaxDevices) return PV_ERR_SHAPE;
+  std::lock_guard<std::mutex> guard(g_scratch_lock);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return hip_fail(e);
+    if (!p) return hip_fail(hipErrorInvalidSymbol);
+    g_scratch_ptr[dev] = p;
+  }
+  *ptr = g_scratch_ptr[dev];
+  return PV_OK;
+}
+
+pv_status pv_masked_attention_static(const pv_sizes* sizes, const void* plan_dev, const void* q,
+                                     const void* k, const void* v, void* out, float* lse,
+                                     int32_t out_dtype, float softmax_scale, float rope_theta,
+                                     void* stream) {
+  PlanHeader h;
+  pv_status st = check_sizes(sizes, &h);
+  if (st != PV_OK) return st;
+  if (!plan_dev || !q || !k || !v || !out) return PV_ERR_NULL;
+  // refused before anything touches the GPU: the fixed array cannot hold this problem
+  int64_t need = 0;
+  st = pv_static_workspace_needed(sizes, &need);
+  if (st != PV_OK) return st;
+  if (need > (int64_t)PV_STATIC_WORKSPACE_BYTES) return PV_ERR_WORKSPACE;
+  st = arch_ok_cached();
+  if (st != PV_OK) return st;
+  void* ws = nullptr;
+  st = static_workspace(&ws);
+  if (st != PV_OK) return st;
+  return attention_call(sizes, plan_dev, q, k, v, out, lse, out_dtype, softmax_scale, rope_theta,
+                        ws, PV_STATIC_WORKSPACE_BYTES, stream, false, true);
+}
+
+pv_status pv_static_workspace_needed(const pv_sizes* sizes, int64_t* bytes_out) {
+  if (!bytes_out) return PV_ERR_NULL;
+  PlanHeader h;
+  pv_status st = check_sizes(sizes, &h);
+  if (st != PV_OK) return st;
+  *bytes_out = attn_workspace_layout(sizes->total_tokens, sizes->padded_keys, sizes->n_seg_tiles,
+                                     sizes->n_q_heads, sizes->n_kv_heads, sizes->head_dim,
+                                     sizes->in_dtype).total_full;
+  return PV_OK;
 }
 
 pv_status pv_segment_attention(const pv_sizes* sizes, const void* plan_dev, const void* q,

@@ -91,6 +91,7 @@ struct AttnWorkspace {
   int64_t off_part;    // bf16 path, segment-only call: partial results of the key pieces, per
                        // (segment tile, kv head, piece, head of the group): float [32][D] then float2 [32]
   int split;           // pieces per work item of the segment-only call (1: no partial results)
+  int64_t total_full;  // bytes the whole-pass call uses (everything before the partial results)
   int64_t total;
 };
 AttnWorkspace attn_workspace_layout(int64_t total_tokens, int64_t padded_keys, int64_t n_seg_tiles,
