@@ -23,10 +23,21 @@ if ROOT not in sys.path:
 
 MFMA_BF16_PEAK_TFLOPS = 2500.0      # MI355X dense bf16 MFMA peak
 
-# HBM bytes per launch of the main kernel from two rocprofv3 --pmc runs (FETCH_SIZE KiB x 2.0, then
-# WRITE_SIZE KiB x 1.0; the factors are what a plain 256 MiB device copy reads on the same
-# counters).  Summaries are under profiles/.  Workloads not listed report null.
-MEASURED_TRAFFIC_BYTES = {"8b": int(25660.6 * 1024 * 2.0 + 24448 * 1024 * 1.0)}
+
+
+def measured_traffic_bytes(workload: str):
+    """HBM bytes per launch of the main kernel as measured under rocprofv3 --pmc (FETCH_SIZE and
+    WRITE_SIZE, each scaled by what the same counter reads for a plain copy of known size): the
+    figure is kept in the counter summary of the workload under profiles/, on a line
+    `traffic_bytes_per_launch: <integer>`, next to the runs it came from.  None if there is no
+    summary for this workload."""
+    import re
+    path = os.path.join(ROOT, "profiles", f"k_attn_bf16_{workload}_counters.md")
+    try:
+        m = re.search(r"^traffic_bytes_per_launch:\s*(\d+)", open(path).read(), flags=re.M)
+    except OSError:
+        return None
+    return int(m.group(1)) if m else None
 
 
 def unmasked_pairs(problem) -> int:
@@ -96,6 +107,11 @@ def main() -> int:
     # the step then reads 4 % slower), and the timed loops still finish in a fraction of a second
     ap.add_argument("--steps", type=int, default=400)
     ap.add_argument("--warmup", type=int, default=200)
+    ap.add_argument("--settle-ms", type=float, default=300.0,
+                    help="untimed steps run for this long before the warm-up so that the clocks of an idle "
+                         "GPU have ramped up when the timed region starts (a step is ~0.1 ms: with a handful "
+                         "of warm-up steps alone the main kernel reads 15-20 %% slower); 0 switches it off; "
+                         "reported as settle_ms, steps and warmup stay as passed")
     ap.add_argument("--workload", default="8b")
     ap.add_argument("--layout", default="appended", choices=["appended", "interleaved"],
                     help="row order of the packed tensors: segments after the draft, or each after its chunk")
@@ -149,6 +165,15 @@ def main() -> int:
         torch.cuda.synchronize()
         del src, dst
 
+    # settle phase: untimed, fixed wall time, reported
+    settle_steps, t_settle = 0, time.perf_counter()
+    while (time.perf_counter() - t_settle) * 1e3 < args.settle_ms:
+        for _ in range(50):
+            step()
+        torch.cuda.synchronize()
+        settle_steps += 50
+    settle_ms = (time.perf_counter() - t_settle) * 1e3 if args.settle_ms > 0 else 0.0
+
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -171,6 +196,10 @@ def main() -> int:
     ks = pv.pv_profile_read_all()          # one duration per step (the last PV_PROFILE_RING of them)
     pv.pv_profile_enable(False)
     kernel_ms = sum(ks) / len(ks)
+    ks_sorted = sorted(ks)
+    kernel_series = {"n": len(ks), "first": ks[0], "last": ks[-1], "min": ks_sorted[0],
+                     "median": ks_sorted[len(ks) // 2], "p90": ks_sorted[min(len(ks) - 1, (9 * len(ks)) // 10)],
+                     "max": ks_sorted[-1]}
 
     # per-call breakdown with events on the launch stream (untimed extra passes)
     def timed(fn, n=50):
@@ -206,12 +235,13 @@ def main() -> int:
     del hid
 
     achieved = eff_flops / (kernel_ms * 1e-3) / 1e12
-    traffic = MEASURED_TRAFFIC_BYTES.get(w.name)
+    traffic = measured_traffic_bytes(w.name) if args.layout == "appended" else None
     line = {
         "metric": "effective masked-attn TFLOP/s (unmasked FLOPs only), whole step: mask plan + attention + readout",
         "value": eff_flops / (ms_per_step * 1e-3) / 1e12,
         "unit": "TFLOP/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "settle_ms": settle_ms, "settle_steps": settle_steps,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": w.name, "layout": args.layout, "batch": pr.batch, "n_q_heads": w.n_q_heads, "n_kv_heads": w.n_kv_heads,
@@ -222,6 +252,7 @@ def main() -> int:
         "verified_prefixes_per_s": pr.total_segments / (ms_per_step * 1e-3),
         "breakdown_ms": {"pv_build_mask": t_build, "pv_masked_attention": t_attn, "pv_first_reject": t_read,
                          "attention_main_kernel": kernel_ms, "step_with_kernel_events": ms_per_step_events},
+        "main_kernel_ms_series": kernel_series,
         "after_step_ms": {"pv_judge_logits_h4096": t_judge, "pv_decide": t_decide},
         "segment_rows_only": {"pv_segment_attention_ms": t_seg, "unmasked_pairs": seg_pairs,
                               "tflops": (4.0 * w.head_dim * w.n_q_heads * seg_pairs / (t_seg * 1e-3) / 1e12) if t_seg else None},
