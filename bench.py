@@ -226,10 +226,15 @@ def main() -> int:
     # earlier pass): key pieces in parallel plus a merge
     seg_pairs = sum(pr.segment_len[b] * (pr.prompt_len[b] + p) + pr.segment_len[b] * (pr.segment_len[b] + 1) // 2
                     for b in range(pr.batch) for p in pr.boundaries[b])
-    t_seg = t_judge = t_decide = None
+    t_seg = t_seg_prepared = t_prepare = t_judge = t_decide = None
     if not args.no_extras:
         if pr.total_segments:
             t_seg = timed(lambda: ver.segment_attention(q, k, v, out, rope_theta=w.rope_theta), n_b)
+            # the same rows over keys prepared once (a second judge pass over the same prefix)
+            t_prepare = timed(lambda: pv.pv_prepare_kv(ver.sizes, ver.plan, k, v, ver.workspace,
+                                                       rope_theta=w.rope_theta), n_b)
+            t_seg_prepared = timed(lambda: pv.pv_segment_attention_prepared(
+                ver.sizes, ver.plan, q, k, v, out, ver.workspace, rope_theta=w.rope_theta), n_b)
         t_judge = timed(lambda: ver.judge_logits(hid, w2), n_b)
         t_decide = timed(lambda: ver.decide(logits, full_lg, pol), n_b)
     del hid
@@ -254,7 +259,8 @@ def main() -> int:
                          "attention_main_kernel": kernel_ms, "step_with_kernel_events": ms_per_step_events},
         "main_kernel_ms_series": kernel_series,
         "after_step_ms": {"pv_judge_logits_h4096": t_judge, "pv_decide": t_decide},
-        "segment_rows_only": {"pv_segment_attention_ms": t_seg, "unmasked_pairs": seg_pairs,
+        "segment_rows_only": {"pv_segment_attention_ms": t_seg, "pv_prepare_kv_ms": t_prepare,
+                              "pv_segment_attention_prepared_ms": t_seg_prepared, "unmasked_pairs": seg_pairs,
                               "tflops": (4.0 * w.head_dim * w.n_q_heads * seg_pairs / (t_seg * 1e-3) / 1e12) if t_seg else None},
         "attn_tflops": eff_flops / (t_attn * 1e-3) / 1e12,
         "max_abs_output": float(out.float().abs().max()),   # bf16 output spacing grows with |o|

@@ -92,6 +92,7 @@ typedef struct {
   int32_t n_seg_tiles;           /* query tiles that hold at least one segment row */
   int32_t n_quads;               /* groups of four consecutive query tiles of a request; 0 unless
                                     Hq/Hkv is a group size whose kernels take them as work items */
+  int32_t n_short_seg_rows;      /* those of the n_short_rows that are segment rows */
 } pv_sizes;
 
 /* Host only: validates the problem and the head configuration and fills `out`.
@@ -149,6 +150,48 @@ pv_status pv_segment_attention(const pv_sizes* sizes, const void* plan_dev, cons
                                const void* k, const void* v, void* out, float* lse,
                                int32_t out_dtype, float softmax_scale, float rope_theta,
                                void* workspace, int64_t workspace_bytes, void* stream);
+
+/* The two halves of pv_segment_attention as calls of their own, for a judge pass over keys that an
+ * earlier pass already prepared (the serving engine keeps the prompt and draft keys between the
+ * premature verification at T_p tokens and the later passes of appendix "Full pipeline"; Stage 2 of
+ * "Design" calls the passes prefill-only and KV-cache-light), and for K/V that live in a paged cache.
+ *
+ * pv_prepare_kv writes, for the tokens [first_token, last_token) of the packed batch (counted in the
+ * order [prompt | draft | segments] of every request), what the attention kernels read instead of
+ * K and V: the rotary table, K rotated at the plan's positions and V, both re-laid-out per kv head.
+ * Tokens outside the range keep what an earlier call prepared; blocks of 16 consecutive tokens of a
+ * request are written whole (a range that starts inside a block re-prepares that block from K and
+ * V).
+ *   key_capacity     0, or a multiple of 64 >= sizes->padded_keys: the per-head stride of the
+ *                    prepared keys, so that calls under different plans find each other's keys.
+ *                    A draft that grew from T_p to T tokens with the same prompt (one request in
+ *                    the batch: its rows do not move) keeps its first P + T_p prepared keys when
+ *                    both passes use the capacity of the larger one and the second pass
+ *                    prepares first_token = P + T_p onwards.  The workspace then needs
+ *                    pv_prepared_workspace_bytes(sizes, key_capacity) bytes; 0 means the layout
+ *                    and size of pv_segment_attention.
+ *   k, v             device bf16; dense [total_tokens][Hkv][D] (block_table_dev NULL), or a pool of
+ *                    pages [n_pages][page_size][Hkv][D] with block_table_dev: device int32
+ *                    [ceil(total_tokens / page_size)], token row r of the packed batch (caller's
+ *                    row order) living at row block_table[r / page_size] * page_size + r % page_size
+ *   workspace        as for pv_segment_attention; it carries the prepared keys to the next call
+ * pv_segment_attention_prepared is pv_segment_attention without the preparation: the segment rows
+ * against the keys already in `workspace`.  k, v (and the block table) are read only for segment
+ * rows that see at most PV_SHORT_ROW_KEYS keys.  With every token prepared by pv_prepare_kv under
+ * the same plan and rope_theta the result is bit-identical to pv_segment_attention.
+ * bf16 inputs only (PV_ERR_DTYPE otherwise). */
+pv_status pv_prepare_kv(const pv_sizes* sizes, const void* plan_dev, const void* k, const void* v,
+                        const int32_t* block_table_dev, int32_t page_size, int64_t first_token,
+                        int64_t last_token, int64_t key_capacity, float rope_theta,
+                        void* workspace, int64_t workspace_bytes, void* stream);
+pv_status pv_segment_attention_prepared(const pv_sizes* sizes, const void* plan_dev, const void* q,
+                                        const void* k, const void* v,
+                                        const int32_t* block_table_dev, int32_t page_size,
+                                        int64_t key_capacity, void* out, float* lse,
+                                        int32_t out_dtype, float softmax_scale, float rope_theta,
+                                        void* workspace, int64_t workspace_bytes, void* stream);
+/* Host only: workspace bytes of the two calls above for a per-head stride of key_capacity keys. */
+pv_status pv_prepared_workspace_bytes(const pv_sizes* sizes, int64_t key_capacity, int64_t* bytes_out);
 
 /* pv_masked_attention for callers that cannot allocate device memory or keep a workspace of their
  * own (code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): the

@@ -41,7 +41,7 @@ class PvSizes(C.Structure):
                 ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32),
                 ("in_dtype", C.c_int32), ("tile_m", C.c_int32), ("tile_n", C.c_int32),
                 ("n_short_rows", C.c_int32), ("layout", C.c_int32),
-                ("n_seg_tiles", C.c_int32), ("n_quads", C.c_int32)]
+                ("n_seg_tiles", C.c_int32), ("n_quads", C.c_int32), ("n_short_seg_rows", C.c_int32)]
 
 
 PV_MAX_SHORT_CHUNKS = 8
@@ -69,6 +69,13 @@ def _load() -> C.CDLL:
                                         C.c_void_p, C.c_void_p, C.c_int32, C.c_float, C.c_float,
                                         C.c_void_p, C.c_int64, C.c_void_p]
     lib.pv_segment_attention.argtypes = lib.pv_masked_attention.argtypes
+    lib.pv_prepare_kv.argtypes = [P(PvSizes), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32,
+                                  C.c_int64, C.c_int64, C.c_int64, C.c_float, C.c_void_p, C.c_int64, C.c_void_p]
+    lib.pv_segment_attention_prepared.argtypes = [P(PvSizes), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                                  C.c_void_p, C.c_int32, C.c_int64, C.c_void_p, C.c_void_p,
+                                                  C.c_int32, C.c_float, C.c_float, C.c_void_p, C.c_int64,
+                                                  C.c_void_p]
+    lib.pv_prepared_workspace_bytes.argtypes = [P(PvSizes), C.c_int64, P(C.c_int64)]
     lib.pv_masked_attention_static.argtypes = [P(PvSizes), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                                C.c_void_p, C.c_void_p, C.c_int32, C.c_float, C.c_float,
                                                C.c_void_p]
@@ -88,7 +95,8 @@ def _load() -> C.CDLL:
     for name in ("pv_query_sizes", "pv_build_mask", "pv_masked_attention", "pv_segment_attention", "pv_first_reject",
                  "pv_plan_export", "pv_profile_enable", "pv_profile_read", "pv_profile_read_all",
                  "pv_last_hip_error",
-                 "pv_judge_logits", "pv_decide", "pv_margin_from_tau", "pv_masked_attention_static",
+                 "pv_judge_logits", "pv_decide", "pv_margin_from_tau", "pv_masked_attention_static", "pv_prepare_kv", "pv_segment_attention_prepared",
+                 "pv_prepared_workspace_bytes",
                  "pv_static_workspace_needed"):
         getattr(lib, name).restype = C.c_int32
     lib.pv_strerror.argtypes = [C.c_int32]
@@ -190,6 +198,44 @@ def pv_masked_attention(sizes: PvSizes, plan: torch.Tensor, q: torch.Tensor, k: 
               softmax_scale, rope_theta, _ptr(workspace), workspace.numel() * workspace.element_size(),
               _stream()),
            "pv_segment_attention" if segments_only else "pv_masked_attention")
+
+
+def pv_prepare_kv(sizes: PvSizes, plan: torch.Tensor, k: torch.Tensor, v: torch.Tensor,
+                  workspace: torch.Tensor, rope_theta: float = 0.0, first_token: int = 0,
+                  last_token: Optional[int] = None, block_table: Optional[torch.Tensor] = None,
+                  page_size: int = 0, key_capacity: int = 0) -> None:
+    """Prepared keys of the tokens [first_token, last_token) into `workspace`.  k, v: dense
+    [total_tokens, Hkv, D], or a page pool [n_pages, page_size, Hkv, D] with an int32 block table."""
+    if k.dtype != torch.bfloat16 or v.dtype != torch.bfloat16:
+        raise ValueError("k/v must be bfloat16")
+    if block_table is not None and block_table.dtype != torch.int32:
+        raise ValueError("block_table must be int32")
+    last = sizes.total_tokens if last_token is None else last_token
+    _check(lib.pv_prepare_kv(C.byref(sizes), _ptr(plan), _ptr(k), _ptr(v), _ptr(block_table), page_size,
+                             first_token, last, key_capacity, rope_theta, _ptr(workspace),
+                             workspace.numel() * workspace.element_size(), _stream()), "pv_prepare_kv")
+
+
+def pv_segment_attention_prepared(sizes: PvSizes, plan: torch.Tensor, q: torch.Tensor, k: torch.Tensor,
+                                  v: torch.Tensor, out: torch.Tensor, workspace: torch.Tensor,
+                                  lse: Optional[torch.Tensor] = None, softmax_scale: float = 0.0,
+                                  rope_theta: float = 0.0, block_table: Optional[torch.Tensor] = None,
+                                  page_size: int = 0, key_capacity: int = 0) -> None:
+    """Segment rows against the keys pv_prepare_kv left in `workspace`."""
+    out_dtype = PV_F32 if out.dtype == torch.float32 else PV_BF16
+    _check(lib.pv_segment_attention_prepared(C.byref(sizes), _ptr(plan), _ptr(q), _ptr(k), _ptr(v),
+                                             _ptr(block_table), page_size, key_capacity, _ptr(out), _ptr(lse),
+                                             out_dtype,
+                                             softmax_scale, rope_theta, _ptr(workspace),
+                                             workspace.numel() * workspace.element_size(), _stream()),
+           "pv_segment_attention_prepared")
+
+
+def pv_prepared_workspace_bytes(sizes: PvSizes, key_capacity: int = 0) -> int:
+    out = C.c_int64(0)
+    _check(lib.pv_prepared_workspace_bytes(C.byref(sizes), key_capacity, C.byref(out)),
+           "pv_prepared_workspace_bytes")
+    return out.value
 
 
 PV_STATIC_WORKSPACE_BYTES = 32 << 20

@@ -113,7 +113,7 @@ AttnWorkspace attn_workspace_layout(int64_t total_tokens, int64_t padded_keys, i
 
 struct Totals {
   int64_t tokens = 0, segments = 0, max_len = 0, q_tiles = 0, padded_keys = 0, mask_bytes = 0;
-  int64_t short_rows = 0, seg_tiles = 0, quads = 0;
+  int64_t short_rows = 0, short_seg_rows = 0, seg_tiles = 0, quads = 0;
 };
 
 // Rows of request (P, T, S, boundaries) that see at most PV_SHORT_ROW_KEYS keys: the first causal
@@ -151,7 +151,10 @@ static pv_status validate_problem(const pv_problem* p, Totals* t) {
       if (pk < prev || pk > T) return PV_ERR_BOUNDARY;
       prev = pk;
     }
-    for_each_short_row(P, T, K, S, p->boundaries + seg, [&](int64_t) { t->short_rows++; });
+    for_each_short_row(P, T, K, S, p->boundaries + seg, [&](int64_t i) {
+      t->short_rows++;
+      if (i >= P + T) t->short_seg_rows++;
+    });
     seg += K;
     t->tokens += n;
     t->max_len = n > t->max_len ? n : t->max_len;
@@ -188,6 +191,7 @@ static void fill_sizes(const pv_problem* p, const Totals& t, int hq, int hkv, in
   s->n_seg_tiles = (int32_t)t.seg_tiles;
   s->n_quads = h.n_quads;
   s->n_short_rows = (int32_t)t.short_rows;
+  s->n_short_seg_rows = (int32_t)t.short_seg_rows;
   s->layout = p->layout;
   s->plan_bytes = (int64_t)h.total_ints * 4;
   s->dense_mask_bytes = t.mask_bytes;
@@ -206,7 +210,8 @@ static pv_status check_sizes(const pv_sizes* s, PlanHeader* h) {
   if (!s) return PV_ERR_NULL;
   if (s->batch < 1 || s->total_tokens < 1 || s->total_segments < 0 || s->n_q_tiles < 1 ||
       s->tile_m != kTileM || s->tile_n != kTileN || s->padded_keys < s->total_tokens ||
-      s->n_short_rows < 0 || s->n_short_rows > s->total_tokens)
+      s->n_short_rows < 0 || s->n_short_rows > s->total_tokens || s->n_short_seg_rows < 0 ||
+      s->n_short_seg_rows > s->n_short_rows)
     return PV_ERR_SHAPE;
   // the limits pv_query_sizes enforces: every index and offset of the plan stays inside int32
   if (s->batch > (1 << 20) || s->total_tokens > (1ll << 27) || s->padded_keys > (1ll << 27) ||
@@ -276,7 +281,8 @@ pv_status pv_build_mask(const pv_problem* problem, const pv_sizes* sizes, void* 
   if (sizes->batch != problem->batch || sizes->total_tokens != t.tokens ||
       sizes->total_segments != t.segments || sizes->n_q_tiles != t.q_tiles ||
       sizes->padded_keys != t.padded_keys || sizes->dense_mask_bytes != t.mask_bytes ||
-      sizes->n_short_rows != t.short_rows || sizes->layout != problem->layout ||
+      sizes->n_short_rows != t.short_rows || sizes->n_short_seg_rows != t.short_seg_rows ||
+      sizes->layout != problem->layout ||
       sizes->n_seg_tiles != t.seg_tiles ||
       sizes->n_quads != (group_uses_query_tiles(sizes->n_q_heads / sizes->n_kv_heads) ? t.quads : 0))
     return PV_ERR_SHAPE;
@@ -342,29 +348,53 @@ pv_status pv_build_mask(const pv_problem* problem, const pv_sizes* sizes, void* 
   return PV_OK;
 }
 
+// What an attention call does: prepare the keys (rotary table, rotated K, transposed V in the
+// workspace), run the main kernel over prepared keys (with the fp32 evaluation of the short rows), or
+// both.
+enum { kPhasePrepare = 1, kPhaseAttend = 2 };
+
 static pv_status attention_call(const pv_sizes* sizes, const void* plan_dev, const void* q,
                                 const void* k, const void* v, void* out, float* lse,
                                 int32_t out_dtype, float softmax_scale, float rope_theta,
                                 void* workspace, int64_t workspace_bytes, void* stream,
-                                bool segments_only, bool library_workspace = false) {
+                                bool segments_only, bool library_workspace = false,
+                                int phases = kPhasePrepare | kPhaseAttend,
+                                const int32_t* block_table = nullptr, int32_t page_size = 0,
+                                int64_t tok_first = 0, int64_t tok_last = -1,
+                                int64_t key_capacity = 0) {
   PlanHeader h;
   pv_status st = check_sizes(sizes, &h);
   if (st != PV_OK) return st;
-  if (!plan_dev || !q || !k || !v || !out || !workspace) return PV_ERR_NULL;
+  // Prepared keys shared by calls under different plans: the per-head stride of the workspace is
+  // the caller's capacity instead of this plan's padded key count.
+  // (an explicit capacity always selects the capacity-based layout, so that every pass that names the
+  // same capacity finds the same offsets, also the pass whose own key count equals it)
+  const bool own_stride = key_capacity != 0;
+  if (key_capacity == 0) key_capacity = sizes->padded_keys;
+  if (key_capacity < sizes->padded_keys || key_capacity % kTileN != 0 || key_capacity > (1ll << 27))
+    return PV_ERR_SHAPE;
+  const bool attend = (phases & kPhaseAttend) != 0, prepare = (phases & kPhasePrepare) != 0;
+  if (!plan_dev || !k || !v || !workspace) return PV_ERR_NULL;
+  if (attend && (!q || !out)) return PV_ERR_NULL;
   if (out_dtype != PV_BF16 && out_dtype != PV_F32) return PV_ERR_DTYPE;
   if (sizes->in_dtype == PV_F32 && out_dtype != PV_F32) return PV_ERR_DTYPE;
-  if (segments_only && sizes->in_dtype != PV_BF16) return PV_ERR_DTYPE;
+  if ((segments_only || phases != (kPhasePrepare | kPhaseAttend)) && sizes->in_dtype != PV_BF16)
+    return PV_ERR_DTYPE;
   if (!(softmax_scale >= 0.0f) || !std::isfinite(softmax_scale)) return PV_ERR_SHAPE;
   if (!(rope_theta >= 0.0f) || !std::isfinite(rope_theta)) return PV_ERR_SHAPE;
+  if (block_table && page_size < 1) return PV_ERR_SHAPE;
+  if (tok_last < 0) tok_last = sizes->total_tokens;
+  if (tok_first < 0 || tok_first > tok_last || tok_last > sizes->total_tokens) return PV_ERR_SHAPE;
   const int hq = sizes->n_q_heads, hkv = sizes->n_kv_heads, d = sizes->head_dim;
   const AttnWorkspace wl =
-      attn_workspace_layout(sizes->total_tokens, sizes->padded_keys, sizes->n_seg_tiles, hq, hkv, d,
-                            sizes->in_dtype);
+      attn_workspace_layout(own_stride ? key_capacity : sizes->total_tokens, key_capacity,
+                            sizes->n_seg_tiles, hq, hkv, d, sizes->in_dtype);
+  h.padded_keys = (int32_t)key_capacity;          // the kernels take the head stride from their copy of the header
   // a caller's workspace must have the size pv_query_sizes reports (which also covers the
   // segment-only call); the library's own fixed array only has to hold what the whole pass uses
   if (workspace_bytes < (library_workspace ? wl.total_full : wl.total)) return PV_ERR_WORKSPACE;
   if (misaligned(plan_dev) || misaligned(q) || misaligned(k) || misaligned(v) ||
-      misaligned(out) || misaligned(workspace) || ((uintptr_t)lse & 3u))
+      misaligned(out) || misaligned(workspace) || ((uintptr_t)lse & 3u) || ((uintptr_t)block_table & 3u))
     return PV_ERR_ALIGN;
   st = arch_ok_cached();
   if (st != PV_OK) return st;
@@ -385,7 +415,7 @@ static pv_status attention_call(const pv_sizes* sizes, const void* plan_dev, con
   } else {
     hipEvent_t ev0 = nullptr, ev1 = nullptr;
     std::unique_lock<std::mutex> guard(g_profile_lock);
-    const bool profiling = g_profile;
+    const bool profiling = g_profile && attend;
     if (profiling) {
       hipEvent_t* pair = g_ev[g_ev_calls % PV_PROFILE_RING];
       if (!pair[0]) {
@@ -401,8 +431,19 @@ static pv_status attention_call(const pv_sizes* sizes, const void* plan_dev, con
     } else {
       guard.unlock();                               // the ordinary path holds no lock while launching
     }
-    e = launch_attn_bf16((const int32_t*)plan_dev, h, q, k, v, out, lse, hq, hkv, d, out_dtype,
-                         scale, freq, rope, (char*)workspace, wl, segments_only, ev0, ev1, s);
+    // One preparation launch: the key blocks (if asked for) and, when the main kernel follows, the
+    // rows with few keys in fp32.
+    KvArgs kv;
+    kv.k = k; kv.v = v; kv.block_table = block_table; kv.page_size = page_size;
+    e = launch_prep_bf16((const int32_t*)plan_dev, h, kv, hkv, d, freq, rope, (char*)workspace, wl,
+                         prepare, tok_first, tok_last,
+                         // the short rows go with the main kernel; a segment-only pass has none to do
+                         // unless a segment sees almost nothing
+                         attend && (!segments_only || sizes->n_short_seg_rows > 0) ? q : nullptr, out, lse,
+                         hq, scale, out_dtype == PV_F32, segments_only, s);
+    if (e == hipSuccess && attend)
+      e = launch_main_bf16((const int32_t*)plan_dev, h, q, out, lse, hq, hkv, d, out_dtype, scale, rope,
+                           (char*)workspace, wl, segments_only, ev0, ev1, s);
     if (e == hipSuccess && profiling) ++g_ev_calls;
   }
   if (e != hipSuccess) return hip_fail(e);
@@ -474,6 +515,43 @@ pv_status pv_segment_attention(const pv_sizes* sizes, const void* plan_dev, cons
                                void* workspace, int64_t workspace_bytes, void* stream) {
   return attention_call(sizes, plan_dev, q, k, v, out, lse, out_dtype, softmax_scale, rope_theta,
                         workspace, workspace_bytes, stream, true);
+}
+
+pv_status pv_prepare_kv(const pv_sizes* sizes, const void* plan_dev, const void* k, const void* v,
+                        const int32_t* block_table_dev, int32_t page_size, int64_t first_token,
+                        int64_t last_token, int64_t key_capacity, float rope_theta,
+                        void* workspace, int64_t workspace_bytes, void* stream) {
+  if (last_token < 0 || key_capacity < 0) return PV_ERR_SHAPE;
+  return attention_call(sizes, plan_dev, nullptr, k, v, nullptr, nullptr, PV_BF16, 0.0f, rope_theta,
+                        workspace, workspace_bytes, stream, true, false, kPhasePrepare,
+                        block_table_dev, page_size, first_token, last_token, key_capacity);
+}
+
+pv_status pv_prepared_workspace_bytes(const pv_sizes* sizes, int64_t key_capacity, int64_t* bytes_out) {
+  if (!bytes_out) return PV_ERR_NULL;
+  PlanHeader h;
+  pv_status st = check_sizes(sizes, &h);
+  if (st != PV_OK) return st;
+  const bool own_stride = key_capacity != 0;
+  if (key_capacity == 0) key_capacity = sizes->padded_keys;
+  if (key_capacity < sizes->padded_keys || key_capacity % kTileN != 0 || key_capacity > (1ll << 27))
+    return PV_ERR_SHAPE;
+  *bytes_out = attn_workspace_layout(own_stride ? key_capacity : sizes->total_tokens, key_capacity,
+                                     sizes->n_seg_tiles, sizes->n_q_heads, sizes->n_kv_heads,
+                                     sizes->head_dim, sizes->in_dtype).total;
+  return PV_OK;
+}
+
+pv_status pv_segment_attention_prepared(const pv_sizes* sizes, const void* plan_dev, const void* q,
+                                        const void* k, const void* v,
+                                        const int32_t* block_table_dev, int32_t page_size,
+                                        int64_t key_capacity, void* out, float* lse,
+                                        int32_t out_dtype, float softmax_scale, float rope_theta,
+                                        void* workspace, int64_t workspace_bytes, void* stream) {
+  if (key_capacity < 0) return PV_ERR_SHAPE;
+  return attention_call(sizes, plan_dev, q, k, v, out, lse, out_dtype, softmax_scale, rope_theta,
+                        workspace, workspace_bytes, stream, true, false, kPhaseAttend,
+                        block_table_dev, page_size, 0, -1, key_capacity);
 }
 
 pv_status pv_first_reject(const pv_sizes* sizes, const void* plan_dev, const float* logits_dev,

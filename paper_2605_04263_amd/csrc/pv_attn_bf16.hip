@@ -25,6 +25,19 @@
 namespace pv {
 
 // ---------------------------------------------------------------- K/V preparation
+// Where the caller's K and V rows are: one dense tensor each, or (block_table != nullptr) a pool of
+// pages of page_size tokens, token row r of the packed batch living at row
+// block_table[r / page_size] * page_size + r % page_size of the pool.
+struct KvSource {
+  const uint16_t* k;
+  const uint16_t* v;
+  const int32_t* block_table;
+  int page_size;
+  __device__ __forceinline__ int64_t row(int64_t r) const {
+    return block_table ? (int64_t)block_table[r / page_size] * page_size + r % page_size : r;
+  }
+};
+
 struct ShortRowArgs {          // what the fp32 evaluation of the short rows needs beyond k, v, cs
   const uint16_t* q;
   void* out;
@@ -41,8 +54,7 @@ struct ShortRowArgs {          // what the fp32 evaluation of the short rows nee
 // evaluates query head kvh*G + w (+4, ...), lane c owning the rotation pair (c, c + D/2).
 template <int D>
 __device__ void short_row_block(const int32_t* __restrict__ plan, const PlanHeader& h,
-                                const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
-                                const RopeFreq& f, int hkv, bool rope, const ShortRowArgs& a,
+                                const KvSource& src, const RopeFreq& f, int hkv, bool rope, const ShortRowArgs& a,
                                 int4 desc, int kvh, float (*ks)[D], float (*vs)[D]) {
   constexpr int HALF = D / 2;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -73,9 +85,9 @@ __device__ void short_row_block(const int32_t* __restrict__ plan, const PlanHead
     const int e = item / HALF, c = item % HALF;
     const int key = e < n_a ? e : b0 + (e - n_a);
     const int tok = base + (e < n ? key : i);             // clamp to a valid row when predicated off
-    const int64_t tok_row = caller_row(plan, h, tok);
-    const uint16_t* kr = k + (tok_row * hkv + kvh) * D;
-    const uint16_t* vr = v + (tok_row * hkv + kvh) * D;
+    const int64_t tok_row = src.row(caller_row(plan, h, tok));
+    const uint16_t* kr = src.k + (tok_row * hkv + kvh) * D;
+    const uint16_t* vr = src.v + (tok_row * hkv + kvh) * D;
     k_lo[it] = kr[c]; k_hi[it] = kr[c + HALF];
     v_lo[it] = vr[c]; v_hi[it] = vr[c + HALF];
     pos_k[it] = plan[h.off_pos + tok];
@@ -143,13 +155,17 @@ __device__ void short_row_block(const int32_t* __restrict__ plan, const PlanHead
 // grid = one block per (short row, kv head) first (they take longest, so they start first), then
 // blocks of 16 keys x 2 kv heads.  Pad rows (beyond the request) are written as 0 so that masked
 // probabilities (exactly 0) never meet a non-finite value.
+//   n_short_blocks  short-row blocks in this launch (0: none)
+//   key_blocks      whether the launch has key blocks at all (a launch of short rows only has none)
+//   tok_first/last  key blocks that hold no token of the packed range [tok_first, tok_last) leave
+//                   their part of the workspace as it is (keys prepared by an earlier call)
 template <int D>
 __global__ __launch_bounds__(256) void k_prep_kv(const int32_t* __restrict__ plan, PlanHeader h,
-                                                 const uint16_t* __restrict__ k,
-                                                 const uint16_t* __restrict__ v, RopeFreq f,
+                                                 KvSource src, RopeFreq f,
                                                  float2* __restrict__ cs, int hkv, bool rope,
                                                  uint16_t* __restrict__ krot,
-                                                 uint16_t* __restrict__ vt, ShortRowArgs sr) {
+                                                 uint16_t* __restrict__ vt, ShortRowArgs sr,
+                                                 int n_short_blocks, int tok_first, int tok_last) {
   constexpr int HALF = D / 2;
   constexpr int KB = 16;                       // keys per block
   constexpr int HG = 2;                        // kv heads per block
@@ -157,13 +173,12 @@ __global__ __launch_bounds__(256) void k_prep_kv(const int32_t* __restrict__ pla
   constexpr int CS_BYTES = KB * HALF * 8, VS_BYTES = HG * KB * (D / 8 + 1) * 16;
   static_assert(2 * PV_SHORT_ROW_KEYS * D * 4 <= CS_BYTES + VS_BYTES, "short-row tiles must fit");
   __shared__ uint4 lds[(CS_BYTES + VS_BYTES) / 16];
-  const int n_short_blocks = h.n_short_rows * hkv;
   if ((int)blockIdx.x < n_short_blocks) {      // one (short row, kv head) each
     const int idx = (int)blockIdx.x;
     const int4 desc = reinterpret_cast<const int4*>(plan + h.off_short)[idx / hkv];
     const int kvh = idx % hkv;
     float (*ks)[D] = reinterpret_cast<float (*)[D]>(&lds[0]);
-    short_row_block<D>(plan, h, k, v, f, hkv, rope, sr, desc, kvh, ks, ks + PV_SHORT_ROW_KEYS);
+    short_row_block<D>(plan, h, src, f, hkv, rope, sr, desc, kvh, ks, ks + PV_SHORT_ROW_KEYS);
     return;
   }
   float2 (*cs_s)[HALF] = reinterpret_cast<float2 (*)[HALF]>(&lds[0]);                       // cos/sin of the block's tokens
@@ -185,6 +200,12 @@ __global__ __launch_bounds__(256) void k_prep_kv(const int32_t* __restrict__ pla
   const int n_b = plan[h.off_tok_start + b + 1] - tok_base;
   const int key0 = row0 - kp[b];               // first local key of the block
   const int tid = threadIdx.x;
+  // Uniform over the workgroup: rows beyond the request's padding (a head stride larger than this
+  // plan's key count) are never read; a block with tokens runs if one of them is in the requested
+  // range; a block of padding only (zeros, see above) goes with the request's last token.
+  if (row0 >= kp[b + 1]) return;
+  const int first_tok = tok_base + min(key0, n_b - 1), end_tok = tok_base + min(key0 + KB, n_b);
+  if (first_tok >= tok_last || end_tok <= tok_first) return;
 
   // The K and V rows of the block are requested first, so that their latency overlaps the rotary
   // angles below.  V item = (key, head, 16-byte piece); K item = (key, head, group of 8 rotation
@@ -198,7 +219,7 @@ __global__ __launch_bounds__(256) void k_prep_kv(const int32_t* __restrict__ pla
     v_reg[it] = make_uint4(0, 0, 0, 0);
     if (item < nh * KB * (D / 8) && key0 + key < n_b)
       v_reg[it] = *reinterpret_cast<const uint4*>(
-          v + (caller_row(plan, h, tok_base + key0 + key) * hkv + h0 + hl) * D + ch * 8);
+          src.v + (src.row(caller_row(plan, h, tok_base + key0 + key)) * hkv + h0 + hl) * D + ch * 8);
   }
 #pragma unroll
   for (int it = 0; it < KIT; ++it) {
@@ -207,9 +228,9 @@ __global__ __launch_bounds__(256) void k_prep_kv(const int32_t* __restrict__ pla
     k_lo[it] = make_uint4(0, 0, 0, 0);
     k_hi[it] = make_uint4(0, 0, 0, 0);
     if (item < nh * KB * (HALF / 8) && key0 + key < n_b) {
-      const uint16_t* src = k + (caller_row(plan, h, tok_base + key0 + key) * hkv + h0 + hl) * D;
-      k_lo[it] = *reinterpret_cast<const uint4*>(src + c0);
-      k_hi[it] = *reinterpret_cast<const uint4*>(src + c0 + HALF);
+      const uint16_t* kr = src.k + (src.row(caller_row(plan, h, tok_base + key0 + key)) * hkv + h0 + hl) * D;
+      k_lo[it] = *reinterpret_cast<const uint4*>(kr + c0);
+      k_hi[it] = *reinterpret_cast<const uint4*>(kr + c0 + HALF);
     }
   }
   // cos/sin of the rotary angles (fp64 angle reduced to a fraction of a turn, fp32 result), also
@@ -380,9 +401,37 @@ static hipError_t dispatch_g(int G, const int32_t* plan, const PlanHeader& h, co
   return hipErrorInvalidValue;
 }
 
-hipError_t launch_attn_bf16(const int32_t* plan_dev, const PlanHeader& h, const void* q,
-                            const void* k, const void* v, void* out, float* lse, int hq, int hkv,
-                            int d, int out_dtype, float scale, const RopeFreq& freq, bool rope,
+// K/V preparation (key blocks of the token range, and the short rows unless sr.q is null).
+hipError_t launch_prep_bf16(const int32_t* plan_dev, const PlanHeader& h, const KvArgs& kv, int hkv, int d,
+                            const RopeFreq& freq, bool rope, char* ws, const AttnWorkspace& wl,
+                            bool key_blocks, int64_t tok_first, int64_t tok_last, const void* q, void* out,
+                            float* lse, int hq, float scale, bool out_f32, bool segments_only,
+                            hipStream_t s) {
+  float2* cs = reinterpret_cast<float2*>(ws + wl.off_cs);
+  uint16_t* krot = reinterpret_cast<uint16_t*>(ws + wl.off_krot);
+  uint16_t* vt = reinterpret_cast<uint16_t*>(ws + wl.off_vt);
+  KvSource src;
+  src.k = reinterpret_cast<const uint16_t*>(kv.k);
+  src.v = reinterpret_cast<const uint16_t*>(kv.v);
+  src.block_table = kv.block_table;
+  src.page_size = kv.page_size;
+  ShortRowArgs sr;
+  sr.q = reinterpret_cast<const uint16_t*>(q); sr.out = out; sr.lse = lse; sr.hq = hq; sr.scale = scale;
+  sr.out_f32 = out_f32; sr.seg_only = segments_only;
+  const int64_t n_short = q ? (int64_t)h.n_short_rows * hkv : 0;
+  const int64_t n_key = key_blocks ? (int64_t)(h.padded_keys / 16) * ((hkv + 1) / 2) : 0;
+  if (n_short + n_key == 0) return hipSuccess;
+  dim3 grid;
+  if (!grid_1d(n_short + n_key, 256, &grid) || n_short > 0x7fffffff) return hipErrorInvalidConfiguration;
+  const int t0 = (int)tok_first, t1 = (int)tok_last;
+  if (d == 64) k_prep_kv<64><<<grid, dim3(256), 0, s>>>(plan_dev, h, src, freq, cs, hkv, rope, krot, vt, sr, (int)n_short, t0, t1);
+  else k_prep_kv<128><<<grid, dim3(256), 0, s>>>(plan_dev, h, src, freq, cs, hkv, rope, krot, vt, sr, (int)n_short, t0, t1);
+  return hipGetLastError();
+}
+
+// The main kernel over prepared keys (and the merge of the key pieces of the segment-only call).
+hipError_t launch_main_bf16(const int32_t* plan_dev, const PlanHeader& h, const void* q, void* out,
+                            float* lse, int hq, int hkv, int d, int out_dtype, float scale, bool rope,
                             char* ws, const AttnWorkspace& wl, bool segments_only, hipEvent_t ev0,
                             hipEvent_t ev1, hipStream_t s) {
   if (segments_only && h.n_seg_tiles == 0) return hipSuccess;          // no segment anywhere
@@ -391,22 +440,8 @@ hipError_t launch_attn_bf16(const int32_t* plan_dev, const PlanHeader& h, const 
   uint16_t* vt = reinterpret_cast<uint16_t*>(ws + wl.off_vt);
   float* part = reinterpret_cast<float*>(ws + wl.off_part);
   const uint16_t* kq = reinterpret_cast<const uint16_t*>(q);
-  const uint16_t* kk = reinterpret_cast<const uint16_t*>(k);
-  const uint16_t* kv = reinterpret_cast<const uint16_t*>(v);
   const bool out_f32 = out_dtype == PV_F32;
   hipError_t e;
-  {
-    dim3 grid;
-    if (!grid_1d((int64_t)(h.padded_keys / 16) * ((hkv + 1) / 2) + (int64_t)h.n_short_rows * hkv, 256, &grid))
-      return hipErrorInvalidConfiguration;
-    ShortRowArgs sr;
-    sr.q = kq; sr.out = out; sr.lse = lse; sr.hq = hq; sr.scale = scale; sr.out_f32 = out_f32;
-    sr.seg_only = segments_only;
-    if (d == 64) k_prep_kv<64><<<grid, dim3(256), 0, s>>>(plan_dev, h, kk, kv, freq, cs, hkv, rope, krot, vt, sr);
-    else k_prep_kv<128><<<grid, dim3(256), 0, s>>>(plan_dev, h, kk, kv, freq, cs, hkv, rope, krot, vt, sr);
-    e = hipGetLastError();
-    if (e != hipSuccess) return e;
-  }
   const float qscale = scale * 1.4426950408889634f;
   const int split = segments_only ? wl.split : 0;
   if (ev0) { e = hipEventRecord(ev0, s); if (e != hipSuccess) return e; }

@@ -113,9 +113,23 @@ hipError_t launch_attn_f32(const int32_t* plan_dev, const PlanHeader& h, const f
                            const float* k, const float* v, float* out, float* lse, int hq,
                            int hkv, int d, float scale, const RopeFreq& freq, bool rope,
                            char* ws, const AttnWorkspace& wl, hipStream_t s);
-hipError_t launch_attn_bf16(const int32_t* plan_dev, const PlanHeader& h, const void* q,
-                            const void* k, const void* v, void* out, float* lse, int hq, int hkv,
-                            int d, int out_dtype, float scale, const RopeFreq& freq, bool rope,
+// The caller's K and V for the preparation: dense tensors, or a pool of pages with a block table.
+struct KvArgs {
+  const void* k;
+  const void* v;
+  const int32_t* block_table;   // device, or nullptr for dense tensors
+  int page_size;
+};
+// bf16 path, step 1: rotary table, rotated K and transposed V of the tokens [tok_first, tok_last) into
+// the workspace (key_blocks), and the fp32 evaluation of the rows with few keys (q != nullptr).
+hipError_t launch_prep_bf16(const int32_t* plan_dev, const PlanHeader& h, const KvArgs& kv, int hkv, int d,
+                            const RopeFreq& freq, bool rope, char* ws, const AttnWorkspace& wl,
+                            bool key_blocks, int64_t tok_first, int64_t tok_last, const void* q, void* out,
+                            float* lse, int hq, float scale, bool out_f32, bool segments_only,
+                            hipStream_t s);
+// bf16 path, step 2: the main kernel over the prepared keys (whole pass, or segment rows only).
+hipError_t launch_main_bf16(const int32_t* plan_dev, const PlanHeader& h, const void* q, void* out,
+                            float* lse, int hq, int hkv, int d, int out_dtype, float scale, bool rope,
                             char* ws, const AttnWorkspace& wl, bool segments_only, hipEvent_t ev0,
                             hipEvent_t ev1, hipStream_t s);
 

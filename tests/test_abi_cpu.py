@@ -231,3 +231,42 @@ def test_margin_from_tau_host_call():
         assert pv.lib.pv_margin_from_tau(bad, C.byref(out)) == pv.PV_ERR_SHAPE
     assert pv.lib.pv_margin_from_tau(0.9, None) == pv.PV_ERR_NULL
     assert out.value == 7.0
+
+
+def test_prepared_key_calls_validate_on_the_host():
+    p = pv.make_problem([4], [60], [2], [3], [5, 9])
+    st, s = q(p, 8, 2, 128)
+    assert st == pv.PV_OK
+    fake = 0x1000
+    L = pv.lib
+    prep = lambda **kw: L.pv_prepare_kv(C.byref(kw.get("s", s)), fake, kw.get("k", fake), fake, kw.get("bt", None),
+                                        kw.get("ps", 0), kw.get("first", 0), kw.get("last", s.total_tokens),
+                                        kw.get("cap", 0), 0.0, kw.get("ws", fake),
+                                        kw.get("wsb", s.attn_workspace_bytes), None)
+    assert prep(k=None) == pv.PV_ERR_NULL
+    assert prep(ws=None) == pv.PV_ERR_NULL
+    assert prep(first=-1) == pv.PV_ERR_SHAPE
+    assert prep(first=9, last=8) == pv.PV_ERR_SHAPE
+    assert prep(last=s.total_tokens + 1) == pv.PV_ERR_SHAPE
+    assert prep(bt=fake, ps=0) == pv.PV_ERR_SHAPE                       # a block table needs a page size
+    assert prep(bt=fake + 2, ps=16) == pv.PV_ERR_ALIGN
+    assert prep(cap=s.padded_keys - 64) == pv.PV_ERR_SHAPE              # capacity below this plan's keys
+    assert prep(cap=s.padded_keys + 32) == pv.PV_ERR_SHAPE              # not a multiple of the key tile
+    assert prep(wsb=s.attn_workspace_bytes - 1) == pv.PV_ERR_WORKSPACE
+    st32, s32 = q(p, 8, 2, 128, pv.PV_F32)
+    assert prep(s=s32, wsb=s32.attn_workspace_bytes) == pv.PV_ERR_DTYPE  # bf16 inputs only
+    # workspace for a larger head stride: grows with the capacity, equals the ordinary size for 0
+    assert pv.pv_prepared_workspace_bytes(s, 0) == s.attn_workspace_bytes
+    big = pv.pv_prepared_workspace_bytes(s, s.padded_keys + 640)
+    assert big >= s.attn_workspace_bytes + 2 * 2 * 640 * 128 * 2
+    assert prep(cap=s.padded_keys + 640, wsb=big - 1) == pv.PV_ERR_WORKSPACE
+    att = lambda **kw: L.pv_segment_attention_prepared(C.byref(s), fake, kw.get("q", fake), fake, fake, None, 0,
+                                                       kw.get("cap", 0), kw.get("out", fake), None, pv.PV_BF16,
+                                                       0.0, 0.0, fake, s.attn_workspace_bytes, None)
+    assert att(q=None) == pv.PV_ERR_NULL
+    assert att(out=None) == pv.PV_ERR_NULL
+    assert att(cap=-64) == pv.PV_ERR_SHAPE
+    # the count of short segment rows is part of the sizes (a segment that sees almost nothing)
+    assert s.n_short_seg_rows == 6 and s.n_short_rows == 16 + 6         # 4 + 9 + 3 = 16 keys at most
+    far = q(pv.make_problem([4], [60], [2], [3], [30, 60]), 8, 2, 128)[1]
+    assert far.n_short_seg_rows == 0 and far.n_short_rows == 16

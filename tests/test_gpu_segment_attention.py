@@ -112,3 +112,126 @@ def test_ragged_sampled():
 
 def test_70b_sampled():
     check_segments(wl.make("70b"), sample=24)
+
+
+# ---------------------------------------------------------------- prepared keys, paged K/V
+
+def _run_unsplit(ver, w, q, k, v, dtype):
+    out = torch.full(q.shape, 7.25, dtype=dtype, device=q.device)
+    lse = torch.full((w.n_q_heads, w.problem.total_tokens), -3.5, dtype=torch.float32, device=q.device)
+    ver.segment_attention(q, k, v, out, lse=lse, rope_theta=w.rope_theta)
+    torch.cuda.synchronize()
+    return out, lse
+
+
+def _same_bits(a, b):
+    return torch.equal(a.contiguous().view(torch.uint8), b.contiguous().view(torch.uint8))
+
+
+@pytest.mark.parametrize("layout", [0, 1])
+@pytest.mark.parametrize("idx", [0, 1, 3, 5, 6])
+def test_prepared_keys_equal_the_unsplit_call(idx, layout):
+    # pv_prepare_kv + pv_segment_attention_prepared against pv_segment_attention: bit for bit, dense K/V
+    # and K/V scattered over a page pool through a block table
+    pr = dataclasses.replace(PROBLEMS[idx], layout=layout)
+    group, d = [(4, 128), (1, 64), (3, 128), (8, 64), (5, 128)][idx % 5]
+    w = wl.make_custom(pr, group * 2, 2, d, dtype=torch.bfloat16, rope_theta=5e5 if idx % 2 else 0.0, seed=180 + idx)
+    ver = gc.make_verifier(pv, w)
+    ver.build_mask()
+    dev = ver.device
+    q, k, v = w.q.to(dev), w.k.to(dev), w.v.to(dev)
+    n = pr.total_tokens
+    for dtype in (torch.float32, torch.bfloat16):
+        want, want_lse = _run_unsplit(ver, w, q, k, v, dtype)
+        # dense
+        ws = torch.full_like(ver.workspace, 0x5A)
+        pv.pv_prepare_kv(ver.sizes, ver.plan, k, v, ws, rope_theta=w.rope_theta)
+        out = torch.full(q.shape, 7.25, dtype=dtype, device=dev)
+        lse = torch.full_like(want_lse, -3.5)
+        pv.pv_segment_attention_prepared(ver.sizes, ver.plan, q, k, v, out, ws, lse, rope_theta=w.rope_theta)
+        torch.cuda.synchronize()
+        assert _same_bits(out, want) and _same_bits(lse, want_lse)
+        # a second judge pass over the same prepared keys (nothing re-prepared): the same bits again
+        out.fill_(7.25); lse.fill_(-3.5)
+        pv.pv_segment_attention_prepared(ver.sizes, ver.plan, q, k, v, out, ws, lse, rope_theta=w.rope_theta)
+        torch.cuda.synchronize()
+        assert _same_bits(out, want) and _same_bits(lse, want_lse)
+        # paged: pages of 16 tokens in a shuffled pool with spare pages
+        ps = 16
+        n_pages = (n + ps - 1) // ps
+        rng = np.random.default_rng(idx)
+        table = torch.from_numpy(rng.permutation(n_pages + 3)[:n_pages].astype(np.int32)).to(dev)
+        pool_k = torch.full(((n_pages + 3) * ps, w.n_kv_heads, d), float("nan"), dtype=torch.bfloat16, device=dev)
+        pool_v = torch.full_like(pool_k, float("nan"))
+        rows = torch.arange(n, device=dev)
+        dst = table.long()[rows // ps] * ps + rows % ps
+        pool_k[dst] = k
+        pool_v[dst] = v
+        ws2 = torch.full_like(ver.workspace, 0x33)
+        pv.pv_prepare_kv(ver.sizes, ver.plan, pool_k, pool_v, ws2, rope_theta=w.rope_theta, block_table=table, page_size=ps)
+        out.fill_(7.25); lse.fill_(-3.5)
+        pv.pv_segment_attention_prepared(ver.sizes, ver.plan, q, pool_k, pool_v, out, ws2, lse, rope_theta=w.rope_theta,
+                                         block_table=table, page_size=ps)
+        torch.cuda.synchronize()
+        assert _same_bits(out, want) and _same_bits(lse, want_lse)
+
+
+def test_prepared_keys_survive_a_grown_draft():
+    # Premature verification at T_p draft tokens, then the pass over the finished draft (appendix "Full
+    # pipeline", Stage 1 and Stage 4): the second pass prepares only the tokens from P + T_p on and must
+    # give the bits of a call that prepares everything; both are checked against the oracle.
+    P, Tp, T, S = 70, 300, 700, 8
+    early = wl.Problem([P], [Tp], [3], [S], [[100, 200, 300]])
+    late = wl.Problem([P], [T], [6], [S], [[100, 200, 300, 450, 600, 700]])
+    wB = wl.make_custom(late, 8, 2, 128, dtype=torch.bfloat16, rope_theta=5e5, seed=210)
+    wA = wl.make_custom(early, 8, 2, 128, dtype=torch.bfloat16, rope_theta=5e5, seed=211)
+    # the early pass sees the same prompt and the first T_p draft tokens
+    for name in ("q", "k", "v"):
+        getattr(wA, name)[:P + Tp] = getattr(wB, name)[:P + Tp]
+    verA, verB = gc.make_verifier(pv, wA), gc.make_verifier(pv, wB)
+    verA.build_mask(); verB.build_mask()
+    dev = verB.device
+    cap = verB.sizes.padded_keys
+    nbytes = max(pv.pv_prepared_workspace_bytes(verA.sizes, cap), pv.pv_prepared_workspace_bytes(verB.sizes, cap))
+    ws = torch.full((nbytes,), 0x5A, dtype=torch.uint8, device=dev)
+    qA, kA, vA = wA.q.to(dev), wA.k.to(dev), wA.v.to(dev)
+    qB, kB, vB = wB.q.to(dev), wB.k.to(dev), wB.v.to(dev)
+    # early pass
+    pv.pv_prepare_kv(verA.sizes, verA.plan, kA, vA, ws, rope_theta=5e5, key_capacity=cap)
+    outA = torch.zeros(qA.shape, dtype=torch.float32, device=dev)
+    pv.pv_segment_attention_prepared(verA.sizes, verA.plan, qA, kA, vA, outA, ws, rope_theta=5e5, key_capacity=cap)
+    torch.cuda.synchronize()
+    rowsA = segment_rows(early)
+    check_errors(outA[rowsA[0]].double().cpu().numpy(), gc.oracle_attention(wA, rows_per_request=rowsA), bf16_out=False)
+    # late pass: only the new tokens are prepared
+    pv.pv_prepare_kv(verB.sizes, verB.plan, kB, vB, ws, rope_theta=5e5, first_token=P + Tp, key_capacity=cap)
+    outB = torch.zeros(qB.shape, dtype=torch.float32, device=dev)
+    lseB = torch.zeros(wB.n_q_heads, late.total_tokens, dtype=torch.float32, device=dev)
+    pv.pv_segment_attention_prepared(verB.sizes, verB.plan, qB, kB, vB, outB, ws, lseB, rope_theta=5e5, key_capacity=cap)
+    torch.cuda.synchronize()
+    want, want_lse = _run_unsplit(verB, wB, qB, kB, vB, torch.float32)
+    rowsB = segment_rows(late)
+    idx = torch.tensor(rowsB[0], device=dev)
+    assert _same_bits(outB[idx], want[idx]) and _same_bits(lseB[:, idx], want_lse[:, idx])
+    check_errors(outB[idx].double().cpu().numpy(), gc.oracle_attention(wB, rows_per_request=rowsB), bf16_out=False)
+
+
+def test_prepared_8b_and_argument_checks():
+    w = wl.make("8b")
+    ver = gc.make_verifier(pv, w)
+    ver.build_mask()
+    dev = ver.device
+    q, k, v = w.q.to(dev), w.k.to(dev), w.v.to(dev)
+    want, want_lse = _run_unsplit(ver, w, q, k, v, torch.bfloat16)
+    pv.pv_prepare_kv(ver.sizes, ver.plan, k, v, ver.workspace, rope_theta=w.rope_theta)
+    out = torch.full(q.shape, 7.25, dtype=torch.bfloat16, device=dev)
+    lse = torch.full_like(want_lse, -3.5)
+    pv.pv_segment_attention_prepared(ver.sizes, ver.plan, q, k, v, out, ver.workspace, lse, rope_theta=w.rope_theta)
+    torch.cuda.synchronize()
+    assert _same_bits(out, want) and _same_bits(lse, want_lse)
+    for bad in (dict(first_token=-1), dict(first_token=5, last_token=4), dict(last_token=w.problem.total_tokens + 1),
+                dict(key_capacity=ver.sizes.padded_keys - 64), dict(key_capacity=ver.sizes.padded_keys + 1),
+                dict(block_table=torch.zeros(4, dtype=torch.int32, device=dev), page_size=0)):
+        with pytest.raises(pv.PvError) as e:
+            pv.pv_prepare_kv(ver.sizes, ver.plan, k, v, ver.workspace, rope_theta=w.rope_theta, **bad)
+        assert e.value.status == pv.PV_ERR_SHAPE, bad
