@@ -19,6 +19,9 @@ calibration", "Parallel partial verify", "Adopted-prefix length"):
 * `attention`       softmax(mask(Q K^T * scale)) V for one request, no tiling.
 * `*_interleaved`   the same pass in the packing of "Parallel partial verify": every suffix
                     copy (End slot) directly after its chunk instead of after the draft.
+* `decode_e4m3`, `masked_attention_fp8kv`
+                    the same pass with K and V stored as FP8 codes plus a scale per kv head
+                    (the paper's target checkpoints are FP8; reading: see the function).
 * `first_reject`    two-way confidence verdicts (Eq. for p_2w), the last-correct
                     index k* ("Parallel partial verify"), the adopted length L*
                     (Eq. "adopted", with rollback eta = 0 generalised to arbitrary
@@ -246,6 +249,56 @@ def masked_attention(prompt_len, draft_len, num_segments, segment_len, boundarie
         qb = rope(np.asarray(q[start:start + N], dtype=np.float64), pos, rope_theta)
         kb = rope(np.asarray(k[start:start + N], dtype=np.float64), pos, rope_theta)
         vb = np.asarray(v[start:start + N], dtype=np.float64)
+        M = mask_fn(P, T, S, boundaries[b], rows)
+        o, l = attention(qb, kb, vb, M, scale, rows, return_lse=True)
+        outs.append(o)
+        lses.append(l)
+        start += N
+    O = np.concatenate(outs, axis=0)
+    return (O, np.concatenate(lses, axis=0)) if return_lse else O
+
+
+# --------------------------------------------------------------------------- FP8 keys and values
+
+def decode_e4m3(bits: np.ndarray) -> np.ndarray:
+    """Value of every 8-bit code of the OCP FP8 E4M3 format (1 sign, 4 exponent, 3 mantissa bits,
+    bias 7, no infinities, S.1111.111 = NaN), exactly, as fp64.  The targets of the paper's
+    experiments are FP8 checkpoints (Experiments, Setup); this is the storage format such a serving
+    stack keeps K and V in."""
+    b = np.asarray(bits, dtype=np.uint8).astype(np.int64)
+    sign = np.where(b & 0x80, -1.0, 1.0)
+    e = (b >> 3) & 0xF
+    m = b & 0x7
+    sub = (m / 8.0) * 2.0 ** -6                       # exponent field 0: no hidden one
+    nor = (1.0 + m / 8.0) * np.exp2((e - 7).astype(np.float64))
+    val = sign * np.where(e == 0, sub, nor)
+    return np.where((e == 15) & (m == 7), np.nan, val)
+
+
+def masked_attention_fp8kv(prompt_len, draft_len, num_segments, segment_len, boundaries,
+                           q: np.ndarray, k_bits: np.ndarray, v_bits: np.ndarray,
+                           k_scale: np.ndarray, v_scale: np.ndarray, rope_theta: float = 0.0,
+                           scale: Optional[float] = None, rows_per_request=None,
+                           return_lse: bool = False, layout: int = LAYOUT_APPENDED):
+    """The packed pass with K and V held as FP8 E4M3 codes and one fp32 scale per kv head:
+    K[t, h, :] = decode(k_bits[t, h, :]) * k_scale[h], likewise V.  The keys are what a KV cache
+    holds, i.e. already rotated at their positions when they were written: only Q is rotated here,
+    at the plan's positions.  Everything else is `masked_attention`: the same mask, the same
+    positions, untiled fp64 softmax.  q [tokens, Hq, D] holds the values the GPU is given, widened."""
+    mask_fn = dense_mask_interleaved if layout == LAYOUT_INTERLEAVED else dense_mask
+    pos_fn = positions_interleaved if layout == LAYOUT_INTERLEAVED else positions
+    ks = np.asarray(k_scale, dtype=np.float32).astype(np.float64)[None, :, None]
+    vs = np.asarray(v_scale, dtype=np.float32).astype(np.float64)[None, :, None]
+    outs, lses = [], []
+    start = 0
+    for b in range(len(prompt_len)):
+        P, T, K, S = prompt_len[b], draft_len[b], num_segments[b], segment_len[b]
+        N = P + T + K * S
+        rows = None if rows_per_request is None else rows_per_request[b]
+        pos = pos_fn(P, T, S, boundaries[b])
+        qb = rope(np.asarray(q[start:start + N], dtype=np.float64), pos, rope_theta)
+        kb = decode_e4m3(k_bits[start:start + N]) * ks
+        vb = decode_e4m3(v_bits[start:start + N]) * vs
         M = mask_fn(P, T, S, boundaries[b], rows)
         o, l = attention(qb, kb, vb, M, scale, rows, return_lse=True)
         outs.append(o)

@@ -214,6 +214,16 @@ def make_70b(seed: int = 5000, batch: int = 4) -> Workload:
                     _judge_logits(rng, prob), 0.985, seed)
 
 
+def quantize_fp8(x: torch.Tensor):
+    """Storage conversion of a [tokens, heads, D] tensor to FP8 E4M3 codes with one scale per head
+    (scale = largest magnitude of the head / 448, the largest E4M3 value; library rounding).
+    Returns (codes uint8 [tokens, heads, D], scales float32 [heads])."""
+    xf = x.float()
+    scale = (xf.abs().amax(dim=(0, 2)) / 448.0).clamp_min(2.0 ** -20)
+    codes = (xf / scale[None, :, None]).to(torch.float8_e4m3fn).view(torch.uint8)
+    return codes.contiguous(), scale.contiguous()
+
+
 WORKLOADS = {
     "tiny": make_tiny,
     "8b": make_8b,
