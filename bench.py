@@ -8,6 +8,10 @@ duration measured with HIP events on the launch stream inside the timed steps; `
 times the fp64 oracle on the host cores of the same box.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 8b|8b_full_verify|ragged|14b|70b|tiny]
+
+A workload name with the suffix _fp8kv (8b_fp8kv, 70b_fp8kv, ...) is the same batch with K and V stored
+as FP8 E4M3 codes and a scale per kv head, run through pv_masked_attention_fp8kv and priced against the
+FP8 MFMA peak; the headline stays the bf16 `8b` workload.
 """
 from __future__ import annotations
 
@@ -22,6 +26,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 MFMA_BF16_PEAK_TFLOPS = 2500.0      # MI355X dense bf16 MFMA peak
+MFMA_FP8_PEAK_TFLOPS = 5000.0       # MI355X dense fp8 MFMA peak (workloads named *_fp8kv)
 
 
 
@@ -89,9 +94,18 @@ def cpu_baseline(w, eff_flops: float) -> dict:
             mask_fn = orc.dense_mask_interleaved if pr.layout == orc.LAYOUT_INTERLEAVED else orc.dense_mask
             M = mask_fn(pr.prompt_len[b], pr.draft_len[b], pr.segment_len[b], pr.boundaries[b], rows[b])
             pairs += int(M.sum(dtype=np.int64))
+    if w.name.endswith("_fp8kv"):
+        import pv_workloads as wl
+        kc, ksc = wl.quantize_fp8(w.k)
+        vc, vsc = wl.quantize_fp8(w.v)
     t0 = time.perf_counter()
-    orc.masked_attention(pr.prompt_len, pr.draft_len, pr.num_segments, pr.segment_len, pr.boundaries,
-                         q, k, v, rope_theta=w.rope_theta, rows_per_request=rows, layout=pr.layout)
+    if w.name.endswith("_fp8kv"):
+        orc.masked_attention_fp8kv(pr.prompt_len, pr.draft_len, pr.num_segments, pr.segment_len, pr.boundaries,
+                                   q, kc.numpy(), vc.numpy(), ksc.numpy(), vsc.numpy(), rope_theta=w.rope_theta,
+                                   rows_per_request=rows, layout=pr.layout)
+    else:
+        orc.masked_attention(pr.prompt_len, pr.draft_len, pr.num_segments, pr.segment_len, pr.boundaries,
+                             q, k, v, rope_theta=w.rope_theta, rows_per_request=rows, layout=pr.layout)
     orc.first_reject(w.logits.numpy(), pr.num_segments, pr.boundaries, orc.margin_threshold(w.tau), 0)
     dt = time.perf_counter() - t0
     flops = 4.0 * w.head_dim * w.n_q_heads * pairs
@@ -136,7 +150,11 @@ def main() -> int:
         print("bench.py: needs a GPU", file=sys.stderr)
         return 2
     dev = torch.device("cuda:0")
-    w = wl.make(args.workload)
+    fp8kv = args.workload.endswith("_fp8kv")
+    w = wl.make(args.workload[:-6] if fp8kv else args.workload)
+    if fp8kv:
+        import dataclasses
+        w = dataclasses.replace(w, name=args.workload)
     pr = w.problem
     if args.layout == "interleaved":
         import dataclasses
@@ -149,10 +167,20 @@ def main() -> int:
     q, k, v, logits = w.q.to(dev), w.k.to(dev), w.v.to(dev), w.logits.to(dev)
     out = torch.empty_like(q)
     thr = pv.margin_from_tau(w.tau)
+    if fp8kv:
+        kc, ksc = (t.to(dev) for t in wl.quantize_fp8(w.k))
+        vc, vsc = (t.to(dev) for t in wl.quantize_fp8(w.v))
+
+        def attention():
+            pv.pv_masked_attention_fp8kv(ver.sizes, ver.plan, q, kc, vc, ksc, vsc, out, ver.workspace,
+                                         rope_theta=w.rope_theta)
+    else:
+        def attention():
+            ver.attention(q, k, v, out=out, rope_theta=w.rope_theta)
 
     def step():
         ver.build_mask()
-        ver.attention(q, k, v, out=out, rope_theta=w.rope_theta)
+        attention()
         ver.first_reject(logits, thr, 0)
 
     pairs = unmasked_pairs(pr)
@@ -212,7 +240,7 @@ def main() -> int:
         return e0.elapsed_time(e1) / n
     n_b = max(5, min(50, args.steps))
     t_build = timed(ver.build_mask, n_b)
-    t_attn = timed(lambda: ver.attention(q, k, v, out=out, rope_theta=w.rope_theta), n_b)
+    t_attn = timed(attention, n_b)
     t_read = timed(lambda: ver.first_reject(logits, thr, 0), n_b)
 
     # the decision calls that follow the readout (not part of the timed step): lm-head gather of
@@ -227,6 +255,8 @@ def main() -> int:
     seg_pairs = sum(pr.segment_len[b] * (pr.prompt_len[b] + p) + pr.segment_len[b] * (pr.segment_len[b] + 1) // 2
                     for b in range(pr.batch) for p in pr.boundaries[b])
     t_seg = t_seg_prepared = t_prepare = t_judge = t_decide = None
+    if fp8kv:
+        args.no_extras = True
     if not args.no_extras:
         if pr.total_segments:
             t_seg = timed(lambda: ver.segment_attention(q, k, v, out, rope_theta=w.rope_theta), n_b)
@@ -241,6 +271,8 @@ def main() -> int:
 
     achieved = eff_flops / (kernel_ms * 1e-3) / 1e12
     traffic = measured_traffic_bytes(w.name) if args.layout == "appended" else None
+    peak = MFMA_FP8_PEAK_TFLOPS if fp8kv else MFMA_BF16_PEAK_TFLOPS
+    kernel_name = "k_attn_fp8" if fp8kv else "k_attn_bf16"
     line = {
         "metric": "effective masked-attn TFLOP/s (unmasked FLOPs only), whole step: mask plan + attention + readout",
         "value": eff_flops / (ms_per_step * 1e-3) / 1e12,
@@ -248,12 +280,12 @@ def main() -> int:
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "settle_ms": settle_ms, "settle_steps": settle_steps,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16", "data": "synthetic",
+        "dtype": "fp8" if fp8kv else "bf16", "data": "synthetic",
         "config": {"workload": w.name, "layout": args.layout, "batch": pr.batch, "n_q_heads": w.n_q_heads, "n_kv_heads": w.n_kv_heads,
                    "head_dim": w.head_dim, "total_tokens": pr.total_tokens, "total_segments": pr.total_segments,
                    "rope_theta": w.rope_theta, "unmasked_pairs": pairs, "effective_flops": eff_flops,
                    "layers": 1},
-        "pct_bf16_mfma_peak_step": 100.0 * eff_flops / (ms_per_step * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+        "pct_mfma_peak_step": 100.0 * eff_flops / (ms_per_step * 1e-3) / 1e12 / peak,
         "verified_prefixes_per_s": pr.total_segments / (ms_per_step * 1e-3),
         "breakdown_ms": {"pv_build_mask": t_build, "pv_masked_attention": t_attn, "pv_first_reject": t_read,
                          "attention_main_kernel": kernel_ms, "step_with_kernel_events": ms_per_step_events},
@@ -264,9 +296,9 @@ def main() -> int:
                               "tflops": (4.0 * w.head_dim * w.n_q_heads * seg_pairs / (t_seg * 1e-3) / 1e12) if t_seg else None},
         "attn_tflops": eff_flops / (t_attn * 1e-3) / 1e12,
         "max_abs_output": float(out.float().abs().max()),   # bf16 output spacing grows with |o|
-        "roofline": {"bound": "mfma", "kernel": "k_attn_bf16", "achieved": achieved,
-                     "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                     "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": traffic},
+        "roofline": {"bound": "mfma", "kernel": kernel_name, "achieved": achieved,
+                     "peak": peak, "unit": "TFLOP/s",
+                     "frac": achieved / peak, "traffic": traffic},
     }
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(w, eff_flops)

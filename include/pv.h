@@ -151,6 +151,26 @@ pv_status pv_segment_attention(const pv_sizes* sizes, const void* plan_dev, cons
                                int32_t out_dtype, float softmax_scale, float rope_theta,
                                void* workspace, int64_t workspace_bytes, void* stream);
 
+/* pv_masked_attention with K and V held as FP8: OCP E4M3 codes (1 sign, 4 exponent, 3 mantissa bits,
+ * bias 7, no infinities) and one fp32 scale per kv head, K[t][h][:] = decode(code) * k_scale[h] and
+ * likewise V -- the storage of the FP8 serving stack the paper's experiments run on (section
+ * "Experiments", Setup: FP8 checkpoints of the target models).  The keys are what a KV cache holds,
+ * i.e. rotated at their positions when they were written (pv_plan_export gives the positions): only
+ * Q, bf16, is rotated by this call.  Both products run on the FP8 matrix instruction; for that Q is
+ * rounded to E4M3 after rotation (per-row power-of-two scale) and the probabilities are rounded to
+ * E4M3 (the row sum is taken over the rounded values), which is where the tolerance of this path
+ * comes from.  Rows that see at most PV_SHORT_ROW_KEYS keys are evaluated in fp32.
+ *   q               device bf16 [total_tokens][Hq][128]  (head_dim 128 only: PV_ERR_SHAPE otherwise)
+ *   k_fp8, v_fp8    device uint8 [total_tokens][Hkv][128], 16-byte aligned, not modified
+ *   k_scale_dev, v_scale_dev   device float [Hkv]
+ *   out, lse, out_dtype, softmax_scale, rope_theta, workspace   as for pv_masked_attention
+ *                   (sizes from pv_query_sizes with in_dtype PV_BF16) */
+pv_status pv_masked_attention_fp8kv(const pv_sizes* sizes, const void* plan_dev, const void* q,
+                                    const void* k_fp8, const void* v_fp8, const float* k_scale_dev,
+                                    const float* v_scale_dev, void* out, float* lse, int32_t out_dtype,
+                                    float softmax_scale, float rope_theta, void* workspace,
+                                    int64_t workspace_bytes, void* stream);
+
 /* The two halves of pv_segment_attention as calls of their own, for a judge pass over keys that an
  * earlier pass already prepared (the serving engine keeps the prompt and draft keys between the
  * premature verification at T_p tokens and the later passes of appendix "Full pipeline"; Stage 2 of

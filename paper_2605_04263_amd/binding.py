@@ -69,6 +69,9 @@ def _load() -> C.CDLL:
                                         C.c_void_p, C.c_void_p, C.c_int32, C.c_float, C.c_float,
                                         C.c_void_p, C.c_int64, C.c_void_p]
     lib.pv_segment_attention.argtypes = lib.pv_masked_attention.argtypes
+    lib.pv_masked_attention_fp8kv.argtypes = [P(PvSizes), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                              C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32,
+                                              C.c_float, C.c_float, C.c_void_p, C.c_int64, C.c_void_p]
     lib.pv_prepare_kv.argtypes = [P(PvSizes), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32,
                                   C.c_int64, C.c_int64, C.c_int64, C.c_float, C.c_void_p, C.c_int64, C.c_void_p]
     lib.pv_segment_attention_prepared.argtypes = [P(PvSizes), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
@@ -96,7 +99,7 @@ def _load() -> C.CDLL:
                  "pv_plan_export", "pv_profile_enable", "pv_profile_read", "pv_profile_read_all",
                  "pv_last_hip_error",
                  "pv_judge_logits", "pv_decide", "pv_margin_from_tau", "pv_masked_attention_static", "pv_prepare_kv", "pv_segment_attention_prepared",
-                 "pv_prepared_workspace_bytes",
+                 "pv_prepared_workspace_bytes", "pv_masked_attention_fp8kv",
                  "pv_static_workspace_needed"):
         getattr(lib, name).restype = C.c_int32
     lib.pv_strerror.argtypes = [C.c_int32]
@@ -198,6 +201,30 @@ def pv_masked_attention(sizes: PvSizes, plan: torch.Tensor, q: torch.Tensor, k: 
               softmax_scale, rope_theta, _ptr(workspace), workspace.numel() * workspace.element_size(),
               _stream()),
            "pv_segment_attention" if segments_only else "pv_masked_attention")
+
+
+def pv_masked_attention_fp8kv(sizes: PvSizes, plan: torch.Tensor, q: torch.Tensor, k_fp8: torch.Tensor,
+                              v_fp8: torch.Tensor, k_scale: torch.Tensor, v_scale: torch.Tensor,
+                              out: torch.Tensor, workspace: torch.Tensor, lse: Optional[torch.Tensor] = None,
+                              softmax_scale: float = 0.0, rope_theta: float = 0.0) -> None:
+    """K/V as E4M3 codes (uint8 [tokens, Hkv, 128]) with per-head scales (float32 [Hkv]); Q bf16."""
+    n, hq, hkv, d = sizes.total_tokens, sizes.n_q_heads, sizes.n_kv_heads, sizes.head_dim
+    if q.dtype != torch.bfloat16 or tuple(q.shape) != (n, hq, d) or tuple(out.shape) != (n, hq, d):
+        raise ValueError("q must be bfloat16 [total_tokens, Hq, D], out the same shape")
+    for t in (k_fp8, v_fp8):
+        if t.dtype != torch.uint8 or tuple(t.shape) != (n, hkv, d):
+            raise ValueError("k_fp8/v_fp8 must be uint8 [total_tokens, Hkv, D]")
+    for t in (k_scale, v_scale):
+        if t.dtype != torch.float32 or tuple(t.shape) != (hkv,):
+            raise ValueError("k_scale/v_scale must be float32 [Hkv]")
+    if lse is not None and (lse.dtype != torch.float32 or tuple(lse.shape) != (hq, n)):
+        raise ValueError("lse must be float32 [Hq, total_tokens]")
+    out_dtype = PV_F32 if out.dtype == torch.float32 else PV_BF16
+    _check(lib.pv_masked_attention_fp8kv(C.byref(sizes), _ptr(plan), _ptr(q), _ptr(k_fp8), _ptr(v_fp8),
+                                         _ptr(k_scale), _ptr(v_scale), _ptr(out), _ptr(lse), out_dtype,
+                                         softmax_scale, rope_theta, _ptr(workspace),
+                                         workspace.numel() * workspace.element_size(), _stream()),
+           "pv_masked_attention_fp8kv")
 
 
 def pv_prepare_kv(sizes: PvSizes, plan: torch.Tensor, k: torch.Tensor, v: torch.Tensor,

@@ -517,6 +517,60 @@ pv_status pv_segment_attention(const pv_sizes* sizes, const void* plan_dev, cons
                         workspace, workspace_bytes, stream, true);
 }
 
+pv_status pv_masked_attention_fp8kv(const pv_sizes* sizes, const void* plan_dev, const void* q,
+                                    const void* k_fp8, const void* v_fp8, const float* k_scale_dev,
+                                    const float* v_scale_dev, void* out, float* lse, int32_t out_dtype,
+                                    float softmax_scale, float rope_theta, void* workspace,
+                                    int64_t workspace_bytes, void* stream) {
+  PlanHeader h;
+  pv_status st = check_sizes(sizes, &h);
+  if (st != PV_OK) return st;
+  if (!plan_dev || !q || !k_fp8 || !v_fp8 || !k_scale_dev || !v_scale_dev || !out || !workspace)
+    return PV_ERR_NULL;
+  if (sizes->in_dtype != PV_BF16) return PV_ERR_DTYPE;          // Q is bf16
+  if (out_dtype != PV_BF16 && out_dtype != PV_F32) return PV_ERR_DTYPE;
+  if (sizes->head_dim != 128) return PV_ERR_SHAPE;
+  if (!(softmax_scale >= 0.0f) || !std::isfinite(softmax_scale)) return PV_ERR_SHAPE;
+  if (!(rope_theta >= 0.0f) || !std::isfinite(rope_theta)) return PV_ERR_SHAPE;
+  const int hq = sizes->n_q_heads, hkv = sizes->n_kv_heads, d = sizes->head_dim;
+  const AttnWorkspace wl = attn_workspace_layout(sizes->total_tokens, sizes->padded_keys,
+                                                 sizes->n_seg_tiles, hq, hkv, d, PV_BF16);
+  if (workspace_bytes < wl.total) return PV_ERR_WORKSPACE;
+  if (misaligned(plan_dev) || misaligned(q) || misaligned(k_fp8) || misaligned(v_fp8) || misaligned(out) ||
+      misaligned(workspace) || ((uintptr_t)lse & 3u) || ((uintptr_t)k_scale_dev & 3u) ||
+      ((uintptr_t)v_scale_dev & 3u))
+    return PV_ERR_ALIGN;
+  st = arch_ok_cached();
+  if (st != PV_OK) return st;
+  const float scale = softmax_scale == 0.0f ? (float)(1.0 / std::sqrt((double)d)) : softmax_scale;
+  RopeFreq freq;
+  const bool rope = rope_theta > 0.0f;
+  for (int c = 0; c < 64; ++c)
+    freq.inv_freq[c] = rope ? std::pow((double)rope_theta, -2.0 * (double)c / (double)d) : 0.0;
+  hipEvent_t ev0 = nullptr, ev1 = nullptr;
+  std::unique_lock<std::mutex> guard(g_profile_lock);
+  const bool profiling = g_profile;
+  hipError_t e;
+  if (profiling) {
+    hipEvent_t* pair = g_ev[g_ev_calls % PV_PROFILE_RING];
+    for (int i = 0; i < 2; ++i)
+      if (!pair[i]) {
+        e = hipEventCreate(&pair[i]);
+        if (e != hipSuccess) { pair[i] = nullptr; return hip_fail(e); }
+      }
+    ev0 = pair[0];
+    ev1 = pair[1];
+  } else {
+    guard.unlock();
+  }
+  e = launch_attn_fp8((const int32_t*)plan_dev, h, q, k_fp8, v_fp8, k_scale_dev, v_scale_dev, out, lse, hq,
+                      hkv, d, out_dtype, scale, freq, rope, (char*)workspace, wl, ev0, ev1,
+                      (hipStream_t)stream);
+  if (e == hipSuccess && profiling) ++g_ev_calls;
+  if (e != hipSuccess) return hip_fail(e);
+  return PV_OK;
+}
+
 pv_status pv_prepare_kv(const pv_sizes* sizes, const void* plan_dev, const void* k, const void* v,
                         const int32_t* block_table_dev, int32_t page_size, int64_t first_token,
                         int64_t last_token, int64_t key_capacity, float rope_theta,

@@ -133,6 +133,12 @@ hipError_t launch_main_bf16(const int32_t* plan_dev, const PlanHeader& h, const 
                             char* ws, const AttnWorkspace& wl, bool segments_only, hipEvent_t ev0,
                             hipEvent_t ev1, hipStream_t s);
 
+// FP8 K/V path (head_dim 128): preparation, short rows and the main kernel on the FP8 matrix instruction.
+hipError_t launch_attn_fp8(const int32_t* plan_dev, const PlanHeader& h, const void* q, const void* k8,
+                           const void* v8, const float* k_scale, const float* v_scale, void* out, float* lse,
+                           int hq, int hkv, int d, int out_dtype, float scale, const RopeFreq& freq, bool rope,
+                           char* ws, const AttnWorkspace& wl, hipEvent_t ev0, hipEvent_t ev1, hipStream_t s);
+
 // Host-side layout of the plan; shared by pv_query_sizes and pv_build_mask.
 void plan_layout(int batch, int64_t total_tokens, int64_t total_segments, int64_t n_q_tiles,
                  int64_t padded_keys, int64_t n_short_rows, int layout, int64_t n_seg_tiles,
