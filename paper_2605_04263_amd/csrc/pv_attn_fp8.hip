@@ -191,6 +191,29 @@ __global__ __launch_bounds__(256) void k_short_fp8(const int32_t* __restrict__ p
 }
 
 // ---------------------------------------------------------------- main kernel
+// Staging of one step's K and V^T tiles (2 x 512 chunks of 16 bytes) through registers.  Free functions
+// on purpose: a private array captured by a lambda is not kept in registers by the compiler.
+template <int G, int CPT>
+__device__ __forceinline__ void fp8_fetch(uint4 (&st)[CPT], const uint8_t* __restrict__ kw,
+                                          const uint8_t* __restrict__ vw, int64_t off, int tid) {
+  constexpr int CH = kStepKeys * 128 / 16;
+#pragma unroll
+  for (int n = 0; n < CPT; ++n) {
+    // (threads beyond the last chunk repeat it: every register is loaded unconditionally)
+    const int x = min(tid + n * (G * 64), 2 * CH - 1);
+    st[n] = x < CH ? reinterpret_cast<const uint4*>(kw + off)[x] : reinterpret_cast<const uint4*>(vw + off)[x - CH];
+  }
+}
+template <int G, int CPT>
+__device__ __forceinline__ void fp8_commit(const uint4 (&st)[CPT], uint4* __restrict__ buf, int tid) {
+  constexpr int CH = kStepKeys * 128 / 16;
+#pragma unroll
+  for (int n = 0; n < CPT; ++n) {
+    const int x = tid + n * (G * 64);
+    if ((2 * CH) % (G * 64) == 0 || x < 2 * CH) buf[x] = st[n];
+  }
+}
+
 template <int D, int G>
 __global__ __launch_bounds__(G * 64, 2) void k_attn_fp8(
     const int32_t* __restrict__ plan, PlanHeader h, const uint16_t* __restrict__ q,
@@ -284,30 +307,15 @@ __global__ __launch_bounds__(G * 64, 2) void k_attn_fp8(
   auto step_tile = [&](int j) { return j < tile.n_a ? j : tile.jb0 + (j - tile.n_a); };
   // staging through registers: chunk x of the 2 * TILE_CHUNKS of a step (K first, then V^T)
   uint4 st[CPT];
-  auto fetch = [&](int j) {
-    const int64_t off = head_base + (int64_t)step_tile(j) * TILE_BYTES;
-#pragma unroll
-    for (int n = 0; n < CPT; ++n) {
-      const int x = tid + n * (G * 64);
-      if ((2 * TILE_CHUNKS) % (G * 64) == 0 || x < 2 * TILE_CHUNKS)
-        st[n] = x < TILE_CHUNKS ? reinterpret_cast<const uint4*>(kw + off)[x]
-                                : reinterpret_cast<const uint4*>(vw + off)[x - TILE_CHUNKS];
-    }
-  };
-  auto commit = [&](int buf) {
-#pragma unroll
-    for (int n = 0; n < CPT; ++n) {
-      const int x = tid + n * (G * 64);
-      if ((2 * TILE_CHUNKS) % (G * 64) == 0 || x < 2 * TILE_CHUNKS) smem[buf][x] = st[n];
-    }
-  };
-  fetch(0);
-  commit(0);
+  fp8_fetch<G, CPT>(st, kw, vw, head_base + (int64_t)step_tile(0) * TILE_BYTES, tid);
+  fp8_commit<G, CPT>(st, &smem[0][0], tid);
   __syncthreads();
 
   for (int j = 0; j < n_steps; ++j) {
     const int buf = j & 1;
-    if (j + 1 < n_steps) fetch(j + 1);
+    // (the last step fetches its own tile once more instead of branching: a conditional fetch makes
+    // the compiler keep the staging registers in scratch memory)
+    fp8_fetch<G, CPT>(st, kw, vw, head_base + (int64_t)step_tile(min(j + 1, n_steps - 1)) * TILE_BYTES, tid);
     const uint4* kt = &smem[buf][0];
     const uint4* vt = &smem[buf][TILE_CHUNKS];
     // S^T of the two 32-key halves
@@ -378,7 +386,7 @@ __global__ __launch_bounds__(G * 64, 2) void k_attn_fp8(
       o[db] = mfma_fp8(a, pb, o[db]);
     }
     lacc = mfma_fp8(ones, pb, lacc);
-    if (j + 1 < n_steps) commit(buf ^ 1);
+    fp8_commit<G, CPT>(st, &smem[buf ^ 1][0], tid);
     __syncthreads();
   }
 
