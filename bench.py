@@ -30,14 +30,14 @@ MFMA_FP8_PEAK_TFLOPS = 5000.0       # MI355X dense fp8 MFMA peak (workloads name
 
 
 
-def measured_traffic_bytes(workload: str):
+def measured_traffic_bytes(workload: str, kernel: str = "k_attn_bf16"):
     """HBM bytes per launch of the main kernel as measured under rocprofv3 --pmc (FETCH_SIZE and
     WRITE_SIZE, each scaled by what the same counter reads for a plain copy of known size): the
     figure is kept in the counter summary of the workload under profiles/, on a line
     `traffic_bytes_per_launch: <integer>`, next to the runs it came from.  None if there is no
     summary for this workload."""
     import re
-    path = os.path.join(ROOT, "profiles", f"k_attn_bf16_{workload}_counters.md")
+    path = os.path.join(ROOT, "profiles", f"{kernel}_{workload}_counters.md")
     try:
         m = re.search(r"^traffic_bytes_per_launch:\s*(\d+)", open(path).read(), flags=re.M)
     except OSError:
@@ -270,9 +270,9 @@ def main() -> int:
     del hid
 
     achieved = eff_flops / (kernel_ms * 1e-3) / 1e12
-    traffic = measured_traffic_bytes(w.name) if args.layout == "appended" else None
     peak = MFMA_FP8_PEAK_TFLOPS if fp8kv else MFMA_BF16_PEAK_TFLOPS
     kernel_name = "k_attn_fp8" if fp8kv else "k_attn_bf16"
+    traffic = measured_traffic_bytes(w.name, kernel_name) if args.layout == "appended" else None
     line = {
         "metric": "effective masked-attn TFLOP/s (unmasked FLOPs only), whole step: mask plan + attention + readout",
         "value": eff_flops / (ms_per_step * 1e-3) / 1e12,
