@@ -295,6 +295,9 @@ def main() -> int:
                               "pv_segment_attention_prepared_ms": t_seg_prepared, "unmasked_pairs": seg_pairs,
                               "tflops": (4.0 * w.head_dim * w.n_q_heads * seg_pairs / (t_seg * 1e-3) / 1e12) if t_seg else None},
         "attn_tflops": eff_flops / (t_attn * 1e-3) / 1e12,
+        # the whole attention call (K/V preparation + main kernel) against the same peak, next to the
+        # main kernel's own fraction in `roofline`
+        "attention_call_frac": eff_flops / (t_attn * 1e-3) / 1e12 / peak,
         "max_abs_output": float(out.float().abs().max()),   # bf16 output spacing grows with |o|
         "roofline": {"bound": "mfma", "kernel": kernel_name, "achieved": achieved,
                      "peak": peak, "unit": "TFLOP/s",
