@@ -170,16 +170,28 @@ __global__ __launch_bounds__(G * 64, 2) __attribute__((amdgpu_waves_per_eu(2))) 
   // are relative to it.  nmref = -mref is what the exponent adds.
   float nmref = 0.0f, l_run = 0.0f;
   const float esc = FOLD ? 1.0f : qscale;   // FOLD: the scale is already in Q
+  // FOLD: the exponent is score + nmref with nothing to multiply, and the matrix pipe does that
+  // addition: every lane's 16 scores belong to one query row, so S^T accumulates on top of a tile
+  // that holds nmref in all 16 registers (cref) instead of on top of zero, and a score tile is
+  // "biased": it already is the exponent.  A change of the reference (rare) also corrects the
+  // biased tiles that exist at that moment.
+  f32x16 cref;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) cref[r] = 0.0f;
   auto prob = [&](float x) {
-    return __builtin_amdgcn_exp2f(FOLD ? x + nmref : __builtin_fmaf(x, esc, nmref));
+    return __builtin_amdgcn_exp2f(FOLD ? x : __builtin_fmaf(x, esc, nmref));
   };
   auto qk = [&](f32x16& acc) {
+    if constexpr (FOLD) {
+      acc = cref;
+    } else {
 #pragma unroll
-    for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
+      for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
+    }
 #pragma unroll
     for (int t = 0; t < KT; ++t) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[t], qf[t], acc, 0, 0, 0);
   };
-  auto apply_mask = [&](f32x16& sc, int key0) {
+  auto apply_mask = [&](f32x16& sc, int key0) __attribute__((always_inline)) {
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
       const int key = key0 + 8 * (r / 4) + 4 * hh + (r % 4);
@@ -189,7 +201,7 @@ __global__ __launch_bounds__(G * 64, 2) __attribute__((amdgpu_waves_per_eu(2))) 
   };
   // p rounded to bf16 once; the row sum is taken over the rounded values (v_dot2c with a pair of
   // ones), so that O is an exact convex combination of V rows with the weights the MFMA sees
-  auto probs = [&](const f32x16& sc, unsigned (&pw)[8]) {
+  auto probs = [&](const f32x16& sc, unsigned (&pw)[8]) __attribute__((always_inline)) {
     float rs = 0.0f;
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
@@ -207,18 +219,25 @@ __global__ __launch_bounds__(G * 64, 2) __attribute__((amdgpu_waves_per_eu(2))) 
   // visible key, or scores drifting by more than 40 octaves.  The reference moves to this step's
   // row maximum, but never so far down that the history (l, O) would leave fp32 range:
   // mref_new >= mref + log2(l) - 20.  `sc` are the scores being exponentiated.  Both half-waves of
-  // a row take identical decisions.
-  auto recentre = [&](const f32x16& sc, unsigned (&pw)[8]) {
+  // a row take identical decisions.  `other` is the score tile of the step after `sc`'s (FOLD: it is
+  // biased with the old reference as well).
+  auto recentre = [&](f32x16& sc, unsigned (&pw)[8], f32x16& other) __attribute__((always_inline)) {
     float mx = sc[0];
 #pragma unroll
     for (int r = 1; r < 16; ++r) mx = fmaxf(mx, sc[r]);
     mx = pair_max(mx);
     const float l_tot = pair_sum(l_run);
     if (mx > -INFINITY && mx < INFINITY) {      // rows with no visible key keep their reference
-      float nm_new = -mx * esc, alpha = 0.0f;   // empty history: nothing to rescale
+      // FOLD: mx is biased, the row maximum itself is mx - nmref
+      float nm_new = FOLD ? nmref - mx : -mx * esc, alpha = 0.0f;   // empty history: nothing to rescale
       if (l_tot > 0.0f) {
         nm_new = fminf(nm_new, nmref - (__builtin_amdgcn_logf(l_tot) - 20.0f));
         alpha = __builtin_amdgcn_exp2f(nm_new - nmref);
+      }
+      if constexpr (FOLD) {
+        const float delta = nm_new - nmref;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) { sc[r] += delta; other[r] += delta; cref[r] = nm_new; }
       }
       nmref = nm_new;
       l_run *= alpha;
@@ -390,7 +409,7 @@ __global__ __launch_bounds__(G * 64, 2) __attribute__((amdgpu_waves_per_eu(2))) 
       kf[t] = lds_read_b128<decltype(t)::value * 1024>(k_off + sbk);
     });
   }
-  if (out_of_window(rs0)) rs0 = recentre(sA, pA);
+  if (out_of_window(rs0)) rs0 = recentre(sA, pA, sB);
   l_run += rs0;
 
   // One step: O^T += V^T P^T of step j and S^T of step j+2 on the MFMA pipe, the probabilities of
@@ -399,12 +418,21 @@ __global__ __launch_bounds__(G * 64, 2) __attribute__((amdgpu_waves_per_eu(2))) 
   //   s_in  scores of step j+1 (input)          s_out  scores of step j+2 (result)
   //   p_in  probabilities of step j (input)     p_out  probabilities of step j+1 (result)
   int slot_v = min(1, last) % NS, slot_k = min(3, last) % NS;   // slots of step j+1 and step j+3
-  //   steady: both refills of this step exist and the pipeline is full, so the wait is a constant
-  //           and the staging loads are issued from inside the MFMA block (no branch splits it)
+  //   kSteady     both refills of this step exist and the pipeline is full: the wait is a constant and
+  //               the staging loads are issued from inside the MFMA block (no branch splits it)
+  //   kFill       both refills exist, the pipeline is still filling: staging as in steady state, the
+  //               wait counted at run time
+  //   kDrain      nothing is left to stage: no staging code, and the wait is for every load
+  //   kGeneric    anything else: counts and staging decided at run time.  kPartial is the same code
+  //               under a second name for the steps in which only some refills are left: one copy
+  //               of the step per loop (the compiler kept the step's registers out of scratch memory
+  //               that way, and not with one copy called from two loops)
+  constexpr int kGeneric = 0, kSteady = 1, kFill = 2, kDrain = 3, kPartial = 4;
   int sj = 0;                                           // j % NS
   auto step = [&](int j, f32x16& s_in, f32x16& s_out, unsigned (&p_in)[8], unsigned (&p_out)[8],
-                  auto last_of_pair, auto steady) {
-    constexpr bool STEADY = decltype(steady)::value;
+                  auto last_of_pair, auto mode) __attribute__((always_inline)) {
+    constexpr int MODE = decltype(mode)::value;
+    constexpr bool STEADY = MODE == kSteady || MODE == kFill;   // staging from inside the MFMA block
     const bool have1 = !decltype(last_of_pair)::value || j + 1 <= last;
     if (have1) {
       const int key0 = step_key0(j + 1);
@@ -427,7 +455,7 @@ __global__ __launch_bounds__(G * 64, 2) __attribute__((amdgpu_waves_per_eu(2))) 
     float ea[16], ex[16];                              // exponent arguments, exponentials
     auto v_arg = [&](auto i) {
       constexpr int I = decltype(i)::value;
-      if constexpr (I < 16) ea[I] = FOLD ? s_in[I] + nmref : __builtin_fmaf(s_in[I], esc, nmref);
+      if constexpr (I < 16) ea[I] = FOLD ? s_in[I] : __builtin_fmaf(s_in[I], esc, nmref);
     };
     auto v_exp = [&](auto i) {
       constexpr int I = decltype(i)::value;
@@ -490,11 +518,15 @@ __global__ __launch_bounds__(G * 64, 2) __attribute__((amdgpu_waves_per_eu(2))) 
     };
     auto mfma_qk = [&](auto t) {
       constexpr int T = decltype(t)::value;
-      if constexpr (T == 0) {
+      if constexpr (T == 0 && FOLD) {
+        s_out = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[t], qf[t], cref, 0, 0, 0);
+      } else {
+        if constexpr (T == 0) {
 #pragma unroll
-        for (int r = 0; r < 16; ++r) s_out[r] = 0.0f;   // becomes the constant-zero accumulator input
+          for (int r = 0; r < 16; ++r) s_out[r] = 0.0f;   // becomes the constant-zero accumulator input
+        }
+        s_out = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[t], qf[t], s_out, 0, 0, 0);
       }
-      s_out = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[t], qf[t], s_out, 0, 0, 0);
     };
     auto wait_operand = [&](bf16x8& r, auto n) {
       constexpr int N = decltype(n)::value;
@@ -533,8 +565,10 @@ __global__ __launch_bounds__(G * 64, 2) __attribute__((amdgpu_waves_per_eu(2))) 
     // (step j+2) can be refilled.  Steps up to j+3 (K) and j+1 (V^T) must be visible; everything
     // issued after them may stay in flight:
     //   K(j+4) .. K(j+1+NS) and V^T(j+2) .. V^T(j+NS-1), as far as they exist and were issued.
-    if constexpr (STEADY && (2 * NS - 4) * HPW + 2 * NREP <= 63) {
+    if constexpr (MODE == kSteady && (2 * NS - 4) * HPW + 2 * NREP <= 63) {
       __builtin_amdgcn_s_waitcnt(vmcnt_imm((2 * NS - 4) * HPW));
+    } else if constexpr (MODE == kDrain) {
+      __builtin_amdgcn_s_waitcnt(0x0f70);              // vmcnt(0)
     } else {
       const int cnt_k = min(NS - 2, j + 2), cnt_v = min(NS - 2, j);
       const int none_k = min(max(j + 1 + NS - last, 0), cnt_k);
@@ -542,7 +576,7 @@ __global__ __launch_bounds__(G * 64, 2) __attribute__((amdgpu_waves_per_eu(2))) 
       wait_slots(std::integral_constant<int, 2 * NS - 4>{}, cnt_k - none_k + cnt_v - none_v);
     }
     __builtin_amdgcn_s_barrier();
-    if constexpr (!STEADY) {
+    if constexpr (MODE == kGeneric || MODE == kPartial) {
       if (j + 2 + NS <= last) stage_k_to(j + 2 + NS, slot_ks);
       if (j + NS <= last) stage_v_to(j + NS, sj);
     }
@@ -569,29 +603,31 @@ __global__ __launch_bounds__(G * 64, 2) __attribute__((amdgpu_waves_per_eu(2))) 
     asm volatile("" : "+v"(rs));                      // the row sum belongs to this block
     __builtin_amdgcn_sched_barrier(0);
     if (have1) {
-      if (__builtin_expect(out_of_window(rs), 0)) rs = recentre(s_in, p_out);
+      if (__builtin_expect(out_of_window(rs), 0)) rs = recentre(s_in, p_out, s_out);
       l_run += rs;
     }
     slot_v = (j + 2 <= last) ? (slot_v + 1 == NS ? 0 : slot_v + 1) : slot_v;
     slot_k = (j + 4 <= last) ? (slot_k + 1 == NS ? 0 : slot_k + 1) : slot_k;
     sj = sj + 1 == NS ? 0 : sj + 1;
   };
-  // Three loops over pairs of steps: filling the pipeline, steady state (the pipeline is full,
-  // j >= NS - 2, and step j + 1 still refills a K slot, j + 3 + NS <= last), draining.
+  // Loops over pairs of steps: filling the pipeline (j < JS), steady state (the pipeline is full,
+  // j >= NS - 2, and step j + 1 still refills a K slot, j + 3 + NS <= last), the few steps in which
+  // some but not all refills are left, and draining (nothing left to stage).  An item long enough
+  // to reach steady state fills with the staging inside the MFMA block as well.
   constexpr int JS = (NS - 2 + 1) & ~1;
+  auto pair_of_steps = [&](int j, auto mode) __attribute__((always_inline)) {
+    step(j, sB, sA, pA, pB, std::false_type{}, mode);
+    step(j + 1, sA, sB, pB, pA, std::true_type{}, mode);
+  };
   int j = 0;
-  for (; j < n_steps && j < JS; j += 2) {
-    step(j, sB, sA, pA, pB, std::false_type{}, std::false_type{});
-    step(j + 1, sA, sB, pB, pA, std::true_type{}, std::false_type{});
+  if (JS + 3 + NS <= last) {
+#pragma nounroll
+    for (; j < JS; j += 2) pair_of_steps(j, std::integral_constant<int, kFill>{});
   }
-  for (; j + 3 + NS <= last; j += 2) {
-    step(j, sB, sA, pA, pB, std::false_type{}, std::true_type{});
-    step(j + 1, sA, sB, pB, pA, std::true_type{}, std::true_type{});
-  }
-  for (; j < n_steps; j += 2) {
-    step(j, sB, sA, pA, pB, std::false_type{}, std::false_type{});
-    step(j + 1, sA, sB, pB, pA, std::true_type{}, std::false_type{});
-  }
+  for (; j < n_steps && j < JS; j += 2) pair_of_steps(j, std::integral_constant<int, kGeneric>{});
+  for (; j + 3 + NS <= last; j += 2) pair_of_steps(j, std::integral_constant<int, kSteady>{});
+  for (; j < n_steps && j + NS <= last; j += 2) pair_of_steps(j, std::integral_constant<int, kPartial>{});
+  for (; j < n_steps; j += 2) pair_of_steps(j, std::integral_constant<int, kDrain>{});
   wait_kv();
 
   // ---- epilogue: normalise, then transpose through LDS so that every output row leaves as one
