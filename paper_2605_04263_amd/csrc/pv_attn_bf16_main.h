@@ -428,21 +428,38 @@ __global__ __launch_bounds__(G * 64, 2) __attribute__((amdgpu_waves_per_eu(2))) 
   //               of the step per loop (the compiler kept the step's registers out of scratch memory
   //               that way, and not with one copy called from two loops)
   constexpr int kGeneric = 0, kSteady = 1, kFill = 2, kDrain = 3, kPartial = 4;
+  // Steady state runs in whole periods of the slot rotation as long as it can (PP pairs of steps,
+  // unrolled): a step at position SP = 2 p + e of a period knows its slots at compile time, so the
+  // LDS addresses are immediates, and it finds its staging sources by advancing two byte offsets
+  // instead of looking the key tile up.  SP = -1: slots and sources computed at run time.
+  constexpr int JS = (NS - 2 + 1) & ~1;                 // first step of steady state
+  constexpr int PP = (NS % 2) ? NS : NS / 2;
+  constexpr unsigned HALF = 32 * D * 2;                 // bytes of one step's K (or V^T) rows
+  // steps from s_mask on hold keys that some row does not see (keys rise with the step)
+  const int idx_mask = mine.n_full < tile.n_a ? mine.n_full : tile.n_a + max(0, mine.n_full - tile.jb0);
+  const int s_mask = 2 * (idx_mask - kt0);
+  // step s_jump is the first one of the second listed range: its rows lie gap_bytes further on
+  const int s_jump = 2 * (tile.n_a - kt0);
+  const unsigned gap_bytes = (unsigned)(tile.jb0 - tile.n_a) * (64 * D * 2);
+  unsigned off_k = 0, off_v = 0;                        // sources of steps j+2+NS and j+NS (unrolled loop)
+  int jrel = 0, mrel = 0;                               // s_jump and s_mask relative to the period's first step
   int sj = 0;                                           // j % NS
   auto step = [&](int j, f32x16& s_in, f32x16& s_out, unsigned (&p_in)[8], unsigned (&p_out)[8],
-                  auto last_of_pair, auto mode) __attribute__((always_inline)) {
+                  auto last_of_pair, auto mode, auto pos) __attribute__((always_inline)) {
     constexpr int MODE = decltype(mode)::value;
+    constexpr int SP = decltype(pos)::value;
+    constexpr bool ST = SP >= 0;                         // slots known at compile time
+    static_assert(!ST || MODE == kSteady, "whole periods run in steady state only");
+    constexpr int PH = ST ? (JS + SP) % NS : 0;          // j % NS
     constexpr bool STEADY = MODE == kSteady || MODE == kFill;   // staging from inside the MFMA block
-    const bool have1 = !decltype(last_of_pair)::value || j + 1 <= last;
-    if (have1) {
-      const int key0 = step_key0(j + 1);
-      if (__builtin_expect(key0 >= mine.n_full * 64, 0)) apply_mask(s_in, key0);
-    }
-    const int slot_ks = sj + 2 >= NS ? sj + 2 - NS : sj + 2;   // (j + 2) % NS
+    const bool have1 = ST || !decltype(last_of_pair)::value || j + 1 <= last;
+    if (__builtin_expect(ST ? mrel <= 1 + SP : have1 && j + 1 >= s_mask, 0)) apply_mask(s_in, step_key0(j + 1));
+    const int slot_ks = ST ? (PH + 2) % NS : sj + 2 >= NS ? sj + 2 - NS : sj + 2;   // (j + 2) % NS
     const bf16x8 pfa = as_bf16x8(make_uint4(p_in[0], p_in[1], p_in[2], p_in[3]));
     const bf16x8 pfb = as_bf16x8(make_uint4(p_in[4], p_in[5], p_in[6], p_in[7]));
     float rs = 0.0f;
-    const unsigned sbv = (unsigned)slot_v * SLOT_BYTES, sbk = (unsigned)slot_k * SLOT_BYTES;
+    constexpr unsigned SBV = ST ? ((PH + 1) % NS) * SLOT_BYTES : 0, SBK = ST ? ((PH + 3) % NS) * SLOT_BYTES : 0;
+    const unsigned sbv = ST ? 0u : (unsigned)slot_v * SLOT_BYTES, sbk = ST ? 0u : (unsigned)slot_k * SLOT_BYTES;
     // The step is 2 KT groups of one MFMA, at most one operand refill and a share of the VALU
     // work, and the issue order is fixed group by group.  (Left to itself the scheduler clusters
     // the MFMAs, and the VALU work then runs while the matrix pipe idles.)  The wave issues in
@@ -459,7 +476,10 @@ __global__ __launch_bounds__(G * 64, 2) __attribute__((amdgpu_waves_per_eu(2))) 
     };
     auto v_exp = [&](auto i) {
       constexpr int I = decltype(i)::value;
-      if constexpr (I < 16) ex[I] = __builtin_amdgcn_exp2f(ea[I]);
+      if constexpr (I < 16) {
+        ex[I] = __builtin_amdgcn_exp2f(ea[I]);
+        asm volatile("" :: "v"(ex[I]));                // a use in this group: not sunk to the pack
+      }
     };
     auto valu_group = [&](auto g) {                    // the VALU share of group g (g = -1: before)
       constexpr int GI = decltype(g)::value;
@@ -491,12 +511,20 @@ __global__ __launch_bounds__(G * 64, 2) __attribute__((amdgpu_waves_per_eu(2))) 
     };
     const char* src_k = nullptr;
     const char* src_v = nullptr;
-    if constexpr (STEADY) {
+    if constexpr (ST) {
+      src_k = krot_b + off_k;
+      src_v = vt_b + off_v;
+      // on to the next step: the other half of the key tile, or the first half of the next listed one
+      constexpr int E = SP & 1;
+      constexpr bool K_ODD = ((NS + E) & 1) != 0, V_ODD = K_ODD;      // parity of steps j+2+NS and j+NS
+      off_k += HALF + (K_ODD && jrel == SP + 3 + NS ? gap_bytes : 0u);
+      off_v += HALF + (V_ODD && jrel == SP + 1 + NS ? gap_bytes : 0u);
+    } else if constexpr (STEADY) {
       src_k = krot_b + (int64_t)step_key0(j + 2 + NS) * (D * 2);
       src_v = vt_b + (int64_t)step_key0(j + NS) * (D * 2);
     }
     const unsigned lds_ks = smem_base + (unsigned)slot_ks * SLOT_BYTES;
-    const unsigned lds_vs = vring + (unsigned)sj * SLOT_BYTES;
+    const unsigned lds_vs = vring + (unsigned)(ST ? PH : sj) * SLOT_BYTES;
     // The 2 NREP staging instructions of this step (K slot first, then V^T slot) are spread evenly
     // over the body groups, the first one in the first group: instruction X goes to group
     // floor(X * BG / (2 NREP)).  (Measured at D = 128, G = 4: four instructions in groups 0, 3, 6, 9
@@ -535,11 +563,11 @@ __global__ __launch_bounds__(G * 64, 2) __attribute__((amdgpu_waves_per_eu(2))) 
     auto refill_v = [&](auto t) {
       constexpr int T = decltype(t)::value;
       constexpr int uu = T / DB, db = T % DB;
-      lds_refill_b128<(uu * 2 * D + db * 32) * 16>(vf[uu][db], v_off + sbv);
+      lds_refill_b128<(uu * 2 * D + db * 32) * 16 + SBV>(vf[uu][db], v_off + sbv);
     };
     auto refill_k = [&](auto t) {
       constexpr int T = decltype(t)::value;
-      lds_refill_b128<T * 1024>(kf[t], k_off + sbk);
+      lds_refill_b128<T * 1024 + SBK>(kf[t], k_off + sbk);
     };
 
     static_for<0, SPG>([&](auto k) { v_arg(k); });
@@ -589,11 +617,13 @@ __global__ __launch_bounds__(G * 64, 2) __attribute__((amdgpu_waves_per_eu(2))) 
       constexpr int T = decltype(t)::value;
       constexpr int R = T - HB;                        // 0, 1, ...
       mfma_pv(t);
+      __builtin_amdgcn_sched_barrier(0);               // the MFMA first, its group's other work behind it
       refill_v(t);
       valu_group(std::integral_constant<int, 2 * T>{});
       if constexpr (STEADY) stage_part2(std::integral_constant<int, 2 * R>{});
       __builtin_amdgcn_sched_barrier(0);
       mfma_qk(t);
+      __builtin_amdgcn_sched_barrier(0);
       refill_k(t);
       valu_group(std::integral_constant<int, 2 * T + 1>{});
       if constexpr (STEADY) stage_part2(std::integral_constant<int, 2 * R + 1>{});
@@ -606,18 +636,19 @@ __global__ __launch_bounds__(G * 64, 2) __attribute__((amdgpu_waves_per_eu(2))) 
       if (__builtin_expect(out_of_window(rs), 0)) rs = recentre(s_in, p_out, s_out);
       l_run += rs;
     }
-    slot_v = (j + 2 <= last) ? (slot_v + 1 == NS ? 0 : slot_v + 1) : slot_v;
-    slot_k = (j + 4 <= last) ? (slot_k + 1 == NS ? 0 : slot_k + 1) : slot_k;
-    sj = sj + 1 == NS ? 0 : sj + 1;
+    if constexpr (!ST) {     // (a whole period leaves them as they are)
+      slot_v = (j + 2 <= last) ? (slot_v + 1 == NS ? 0 : slot_v + 1) : slot_v;
+      slot_k = (j + 4 <= last) ? (slot_k + 1 == NS ? 0 : slot_k + 1) : slot_k;
+      sj = sj + 1 == NS ? 0 : sj + 1;
+    }
   };
   // Loops over pairs of steps: filling the pipeline (j < JS), steady state (the pipeline is full,
   // j >= NS - 2, and step j + 1 still refills a K slot, j + 3 + NS <= last), the few steps in which
   // some but not all refills are left, and draining (nothing left to stage).  An item long enough
   // to reach steady state fills with the staging inside the MFMA block as well.
-  constexpr int JS = (NS - 2 + 1) & ~1;
   auto pair_of_steps = [&](int j, auto mode) __attribute__((always_inline)) {
-    step(j, sB, sA, pA, pB, std::false_type{}, mode);
-    step(j + 1, sA, sB, pB, pA, std::true_type{}, mode);
+    step(j, sB, sA, pA, pB, std::false_type{}, mode, std::integral_constant<int, -1>{});
+    step(j + 1, sA, sB, pB, pA, std::true_type{}, mode, std::integral_constant<int, -1>{});
   };
   int j = 0;
   if (JS + 3 + NS <= last) {
@@ -625,6 +656,22 @@ __global__ __launch_bounds__(G * 64, 2) __attribute__((amdgpu_waves_per_eu(2))) 
     for (; j < JS; j += 2) pair_of_steps(j, std::integral_constant<int, kFill>{});
   }
   for (; j < n_steps && j < JS; j += 2) pair_of_steps(j, std::integral_constant<int, kGeneric>{});
+  if (j == JS && j + 2 * PP + 1 + NS <= last) {          // whole periods of the slot rotation
+    off_k = (unsigned)step_key0(j + 2 + NS) * (D * 2);
+    off_v = (unsigned)step_key0(j + NS) * (D * 2);
+    do {
+      jrel = s_jump - j;
+      mrel = s_mask - j;
+      static_for<0, PP>([&](auto p) __attribute__((always_inline)) {
+        constexpr int P2 = 2 * decltype(p)::value;
+        step(j + P2, sB, sA, pA, pB, std::false_type{}, std::integral_constant<int, kSteady>{},
+             std::integral_constant<int, P2>{});
+        step(j + P2 + 1, sA, sB, pB, pA, std::true_type{}, std::integral_constant<int, kSteady>{},
+             std::integral_constant<int, P2 + 1>{});
+      });
+      j += 2 * PP;
+    } while (j + 2 * PP + 1 + NS <= last);
+  }
   for (; j + 3 + NS <= last; j += 2) pair_of_steps(j, std::integral_constant<int, kSteady>{});
   for (; j < n_steps && j + NS <= last; j += 2) pair_of_steps(j, std::integral_constant<int, kPartial>{});
   for (; j < n_steps; j += 2) pair_of_steps(j, std::integral_constant<int, kDrain>{});
