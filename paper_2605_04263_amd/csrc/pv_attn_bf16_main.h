@@ -441,7 +441,9 @@ __global__ __launch_bounds__(G * 64, 2) __attribute__((amdgpu_waves_per_eu(2))) 
   // step s_jump is the first one of the second listed range: its rows lie gap_bytes further on
   const int s_jump = 2 * (tile.n_a - kt0);
   const unsigned gap_bytes = (unsigned)(tile.jb0 - tile.n_a) * (64 * D * 2);
-  unsigned off_k = 0, off_v = 0;                        // sources of steps j+2+NS and j+NS (unrolled loop)
+  // byte offsets of the rows that step j stages (steps j+2+NS and j+NS), advanced by every step
+  unsigned off_k = (unsigned)step_key0(min(2 + NS, last)) * (D * 2);
+  unsigned off_v = (unsigned)step_key0(min(NS, last)) * (D * 2);
   int jrel = 0, mrel = 0;                               // s_jump and s_mask relative to the period's first step
   int sj = 0;                                           // j % NS
   auto step = [&](int j, f32x16& s_in, f32x16& s_out, unsigned (&p_in)[8], unsigned (&p_out)[8],
@@ -511,17 +513,17 @@ __global__ __launch_bounds__(G * 64, 2) __attribute__((amdgpu_waves_per_eu(2))) 
     };
     const char* src_k = nullptr;
     const char* src_v = nullptr;
-    if constexpr (ST) {
-      src_k = krot_b + off_k;
-      src_v = vt_b + off_v;
-      // on to the next step: the other half of the key tile, or the first half of the next listed one
-      constexpr int E = SP & 1;
-      constexpr bool K_ODD = ((NS + E) & 1) != 0, V_ODD = K_ODD;      // parity of steps j+2+NS and j+NS
-      off_k += HALF + (K_ODD && jrel == SP + 3 + NS ? gap_bytes : 0u);
-      off_v += HALF + (V_ODD && jrel == SP + 1 + NS ? gap_bytes : 0u);
-    } else if constexpr (STEADY) {
-      src_k = krot_b + (int64_t)step_key0(j + 2 + NS) * (D * 2);
-      src_v = vt_b + (int64_t)step_key0(j + NS) * (D * 2);
+    src_k = krot_b + off_k;
+    src_v = vt_b + off_v;
+    {
+      // on to the next step: the other half of the key tile, or the first half of the next listed
+      // one, which at step s_jump lies gap_bytes further on.  Steps j+2+NS and j+NS have the parity
+      // of NS + j; j is even for the first step of a pair.
+      constexpr bool ODD = ((NS + (decltype(last_of_pair)::value ? 1 : 0)) & 1) != 0;
+      const bool jump_k = ODD && (ST ? jrel == SP + 3 + NS : j + 3 + NS == s_jump);
+      const bool jump_v = ODD && (ST ? jrel == SP + 1 + NS : j + 1 + NS == s_jump);
+      off_k += HALF + (jump_k ? gap_bytes : 0u);
+      off_v += HALF + (jump_v ? gap_bytes : 0u);
     }
     const unsigned lds_ks = smem_base + (unsigned)slot_ks * SLOT_BYTES;
     const unsigned lds_vs = vring + (unsigned)(ST ? PH : sj) * SLOT_BYTES;
@@ -605,8 +607,8 @@ __global__ __launch_bounds__(G * 64, 2) __attribute__((amdgpu_waves_per_eu(2))) 
     }
     __builtin_amdgcn_s_barrier();
     if constexpr (MODE == kGeneric || MODE == kPartial) {
-      if (j + 2 + NS <= last) stage_k_to(j + 2 + NS, slot_ks);
-      if (j + NS <= last) stage_v_to(j + NS, sj);
+      if (j + 2 + NS <= last) stage_slot(src_k, lds_ks);
+      if (j + NS <= last) stage_slot(src_v, lds_vs);
     }
     __builtin_amdgcn_sched_barrier(0);
     static_for<0, HB>([&](auto t) { refill_v(t); refill_k(t); });
@@ -657,8 +659,6 @@ __global__ __launch_bounds__(G * 64, 2) __attribute__((amdgpu_waves_per_eu(2))) 
   }
   for (; j < n_steps && j < JS; j += 2) pair_of_steps(j, std::integral_constant<int, kGeneric>{});
   if (j == JS && j + 2 * PP + 1 + NS <= last) {          // whole periods of the slot rotation
-    off_k = (unsigned)step_key0(j + 2 + NS) * (D * 2);
-    off_v = (unsigned)step_key0(j + NS) * (D * 2);
     do {
       jrel = s_jump - j;
       mrel = s_mask - j;
