@@ -191,12 +191,20 @@ __global__ __launch_bounds__(G * 64, 2) __attribute__((amdgpu_waves_per_eu(2))) 
 #pragma unroll
     for (int t = 0; t < KT; ++t) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[t], qf[t], acc, 0, 0, 0);
   };
+  // The 16 scores of a lane are keys key0 + 4 hh + c, c = 8 (r / 4) + r % 4, of one query row: the row's
+  // visible keys among the step's 32 become a bit mask (three clamped "low n bits" masks), and every
+  // score is kept or replaced by -inf with a bit-field extract and a bit-field insert.
   auto apply_mask = [&](f32x16& sc, int key0) __attribute__((always_inline)) {
+    const int base = key0 + 4 * hh;
+    auto low_bits = [](int n) {                         // bits [0, n) of 32, n clamped to [0, 32]
+      const unsigned m = (1u << (n & 31)) - 1u;
+      return n <= 0 ? 0u : n >= 32 ? 0xffffffffu : m;
+    };
+    const unsigned vis = low_bits(a_end - base) | (low_bits(i_loc - base + 1) & ~low_bits(b_start - base));
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
-      const int key = key0 + 8 * (r / 4) + 4 * hh + (r % 4);
-      const bool vis = (key < a_end) | ((key >= b_start) & (key <= i_loc));   // branch-free
-      sc[r] = vis ? sc[r] : -INFINITY;
+      const unsigned keep = (unsigned)__builtin_amdgcn_sbfe((int)vis, 8 * (r / 4) + (r % 4), 1);   // all ones or zero
+      sc[r] = __uint_as_float((__float_as_uint(sc[r]) & keep) | (0xff800000u & ~keep));
     }
   };
   // p rounded to bf16 once; the row sum is taken over the rounded values (v_dot2c with a pair of
