@@ -133,6 +133,19 @@ def test_group_sizes_long_rows(group, d):
     check_full(w)
 
 
+# The main kernel runs the middle of a long item in unrolled periods of its K/V ring (10 steps of 32 keys
+# at head size 128, 8 at 64) and finds the rows a step stages by advancing an offset, with one extra gap
+# where a segment row's key list jumps from its prefix to its own segment.  The prefix length moves that
+# jump through every position of a period, and, with a boundary a few tiles before the end of the draft,
+# into the left-over steps behind the periods as well.
+@pytest.mark.parametrize("d,group", [(128, 4), (128, 8), (64, 4)])
+@pytest.mark.parametrize("prompt", [576 + 32 * i for i in range(12)])
+def test_key_list_jump_at_every_period_position(prompt, d, group):
+    pr = wl.Problem([prompt], [96], [3], [40], [[5, 64, 96]])
+    w = wl.make_custom(pr, group, 1, d, dtype=torch.bfloat16, rope_theta=5e5, seed=900 + prompt // 32 + d + group)
+    check_full(w)
+
+
 # Group sizes other than 4 and 8 run as workgroups of four query tiles of one head: ragged batches whose
 # last group of tiles is short, segments shorter and longer than a tile, and tiles that straddle two
 # segments, where the four waves of a workgroup mask with different descriptors.
