@@ -219,12 +219,16 @@ __global__ __launch_bounds__(G * 64, 2) __attribute__((amdgpu_waves_per_eu(2))) 
     }
     return rs;
   };
+  // The window test of a step: its partial row sum `rs` must not exceed 2^40, and the running sum
+  // with it must have reached 2^-40.  (The lower bound is on the total, not on the step: a step
+  // whose keys are all masked for a lane, every step of a diagonal tile for some lane, or whose
+  // scores lie 40 octaves below a healthy history adds nothing, and nothing needs correcting.)
   auto out_of_window = [&](float rs) {
-    return __builtin_amdgcn_ballot_w64(!(rs >= 0x1p-40f && rs <= 0x1p40f)) != 0;
+    return __builtin_amdgcn_ballot_w64(!(l_run + rs >= 0x1p-40f && rs <= 0x1p40f)) != 0;
   };
-  // One exact online-softmax step for the whole wave: taken when a partial row sum is outside
-  // [2^-40, 2^40] (also catches inf/NaN/0).  Rare: first steps of a row, masked steps with no
-  // visible key, or scores drifting by more than 40 octaves.  The reference moves to this step's
+  // One exact online-softmax step for the whole wave: taken when the window test fails (it also
+  // catches inf/NaN, and a running sum still at 0).  Rare: first steps of a row while no key is
+  // visible to it, or scores rising by more than 40 octaves.  The reference moves to this step's
   // row maximum, but never so far down that the history (l, O) would leave fp32 range:
   // mref_new >= mref + log2(l) - 20.  `sc` are the scores being exponentiated.  Both half-waves of
   // a row take identical decisions.  `other` is the score tile of the step after `sc`'s (FOLD: it is
