@@ -1,8 +1,8 @@
 """Compiles the HIP library for gfx950 in-tree (paper_2605_04263_amd/libpv.so).
 
 Every source under csrc/ is one translation unit, except pv_attn_bf16_inst.hip, which is compiled
-once per (head size, set of GQA group sizes): the main attention kernel has three dozen
-instantiations and they build in parallel this way.  Objects go to paper_2605_04263_amd/_build/.
+once per (head size, GQA group size): the main attention kernel has three dozen instantiations
+and they build in parallel this way.  Objects go to paper_2605_04263_amd/_build/.
 """
 from __future__ import annotations
 
@@ -24,7 +24,7 @@ FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-I" + os.path.join(ROOT, "include"), "-I" + CSRC]
 INST_SOURCE = "pv_attn_bf16_inst.hip"
-INST_UNITS = [(d, s) for d in (128, 64) for s in (1, 3, 0, 2)]      # the longest compiles first
+INST_UNITS = [(d, s) for d in (128, 64) for s in range(1, 10)]      # group sizes 1..8, 9 = query tiles
 
 
 def _inputs():
