@@ -336,15 +336,24 @@ __global__ __launch_bounds__(G * 64, 2) void k_attn_fp8(
     }
     const int jt = step_tile(j);
     const int key0 = jt * kStepKeys;
-    if (jt >= tile.n_full) {                               // row predicate (branch-free inside)
+    if (jt >= tile.n_full) {
+      // Row predicate: the keys of half u that this lane holds are key0 + 32 u + 4 hh + c,
+      // c = 8 (r / 4) + r % 4; the row's visible ones among the 32 become a bit mask, and a score
+      // is kept or replaced by -inf with one bit-field extract and one bit-field insert.
+      auto low_bits = [](int n) {                          // bits [0, n) of 32, n clamped to [0, 32]
+        const unsigned m = (1u << (n & 31)) - 1u;
+        return n <= 0 ? 0u : n >= 32 ? 0xffffffffu : m;
+      };
 #pragma unroll
-      for (int u = 0; u < 2; ++u)
+      for (int u = 0; u < 2; ++u) {
+        const int base = key0 + 32 * u + 4 * hh;
+        const unsigned vis = low_bits(a_end - base) | (low_bits(i_loc - base + 1) & ~low_bits(b_start - base));
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-          const int key = key0 + 32 * u + 8 * (r / 4) + 4 * hh + (r % 4);
-          const bool vis = (key < a_end) | ((key >= b_start) & (key <= i_loc));
-          s[u][r] = vis ? s[u][r] : -INFINITY;
+          const unsigned keep = (unsigned)__builtin_amdgcn_sbfe((int)vis, 8 * (r / 4) + (r % 4), 1);
+          s[u][r] = __uint_as_float((__float_as_uint(s[u][r]) & keep) | (0xff800000u & ~keep));
         }
+      }
     }
     // running reference: moved up when this step's largest exponent exceeds it by more than 0.75
     // octave (probabilities scaled by 2^8 then stay below 2^8.75 = 431 < 448, the largest E4M3 value)
