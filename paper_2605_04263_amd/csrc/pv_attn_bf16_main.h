@@ -454,6 +454,7 @@ __global__ __launch_bounds__(G * 64, 2) __attribute__((amdgpu_waves_per_eu(2))) 
   const int s_jump = 2 * (tile.n_a - kt0);
   const unsigned gap_bytes = (unsigned)(tile.jb0 - tile.n_a) * (64 * D * 2);
   // byte offsets of the rows that step j stages (steps j+2+NS and j+NS), advanced by every step
+  // (32 bits: the host admits at most 2^24 keys per request, 2^32 bytes of rows at D = 128)
   unsigned off_k = (unsigned)step_key0(min(2 + NS, last)) * (D * 2);
   unsigned off_v = (unsigned)step_key0(min(NS, last)) * (D * 2);
   int jrel = 0, mrel = 0;                               // s_jump and s_mask relative to the period's first step
