@@ -431,19 +431,22 @@ static pv_status attention_call(const pv_sizes* sizes, const void* plan_dev, con
     } else {
       guard.unlock();                               // the ordinary path holds no lock while launching
     }
-    // One preparation launch: the key blocks (if asked for) and, when the main kernel follows, the
-    // rows with few keys in fp32.
+    // One preparation launch: the key blocks (if asked for) and, when the main kernel follows and
+    // cannot take them itself, the rows with few keys in fp32.  A whole pass that prepares all its
+    // keys in this call (so that the table of rotary angles is complete) leaves them to the main
+    // kernel, where they run as extra workgroups in the tail of the launch.
     KvArgs kv;
     kv.k = k; kv.v = v; kv.block_table = block_table; kv.page_size = page_size;
+    const bool short_in_main = attend && prepare && tok_first == 0 && tok_last == sizes->total_tokens &&
+                               main_kernel_takes_short_rows(h, hq, hkv, segments_only);
     e = launch_prep_bf16((const int32_t*)plan_dev, h, kv, hkv, d, freq, rope, (char*)workspace, wl,
                          prepare, tok_first, tok_last,
-                         // the short rows go with the main kernel; a segment-only pass has none to do
-                         // unless a segment sees almost nothing
-                         attend && (!segments_only || sizes->n_short_seg_rows > 0) ? q : nullptr, out, lse,
-                         hq, scale, out_dtype == PV_F32, segments_only, s);
+                         // a segment-only pass has no short rows to do unless a segment sees almost nothing
+                         attend && !short_in_main && (!segments_only || sizes->n_short_seg_rows > 0) ? q : nullptr,
+                         out, lse, hq, scale, out_dtype == PV_F32, segments_only, s);
     if (e == hipSuccess && attend)
       e = launch_main_bf16((const int32_t*)plan_dev, h, q, out, lse, hq, hkv, d, out_dtype, scale, rope,
-                           (char*)workspace, wl, segments_only, ev0, ev1, s);
+                           (char*)workspace, wl, segments_only, short_in_main ? &kv : nullptr, ev0, ev1, s);
     if (e == hipSuccess && profiling) ++g_ev_calls;
   }
   if (e != hipSuccess) return hip_fail(e);

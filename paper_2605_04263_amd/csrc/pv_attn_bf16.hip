@@ -21,137 +21,11 @@
 // accumulator registers of S^T (the key order inside a slab is chosen to make that a pure
 // register repack).
 #include "pv_attn_common.h"
+#include "pv_short_rows.h"
 
 namespace pv {
 
 // ---------------------------------------------------------------- K/V preparation
-// Where the caller's K and V rows are: one dense tensor each, or (block_table != nullptr) a pool of
-// pages of page_size tokens, token row r of the packed batch living at row
-// block_table[r / page_size] * page_size + r % page_size of the pool.
-struct KvSource {
-  const uint16_t* k;
-  const uint16_t* v;
-  const int32_t* block_table;
-  int page_size;
-  __device__ __forceinline__ int64_t row(int64_t r) const {
-    return block_table ? (int64_t)block_table[r / page_size] * page_size + r % page_size : r;
-  }
-};
-
-struct ShortRowArgs {          // what the fp32 evaluation of the short rows needs beyond k, v, cs
-  const uint16_t* q;
-  void* out;
-  float* lse;
-  int hq;
-  float scale;
-  bool out_f32;
-  bool seg_only;       // segment-only call: rows of prompt and draft tokens are left alone
-};
-
-// Rows with at most PV_SHORT_ROW_KEYS visible keys, in plain fp32 (the main kernel does not store
-// them).  One workgroup per (row, kv head): all threads first rotate the row's visible keys into
-// LDS (one rotary angle per thread and pass instead of one per key and lane), then wave w
-// evaluates query head kvh*G + w (+4, ...), lane c owning the rotation pair (c, c + D/2).
-template <int D>
-__device__ void short_row_block(const int32_t* __restrict__ plan, const PlanHeader& h,
-                                const KvSource& src, const RopeFreq& f, int hkv, bool rope, const ShortRowArgs& a,
-                                int4 desc, int kvh, float (*ks)[D], float (*vs)[D]) {
-  constexpr int HALF = D / 2;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int G = a.hq / hkv;
-  // desc = (packed row, first row of its request, a_end, b_start), written by the host
-  const int g = desc.x, base = desc.y, i = g - base;
-  const int a_end = desc.z, b_start = desc.w;
-  if (a.seg_only && b_start == 0) return;      // a prompt or draft row (uniform over the workgroup)
-  // Visible keys: [0, a_end) then [max(b_start, a_end), i]; at most PV_SHORT_ROW_KEYS of them.
-  const int n_a = min(a_end, (int)PV_SHORT_ROW_KEYS);
-  const int b0 = max(b_start, a_end);
-  const int n = min(n_a + max(i - b0 + 1, 0), (int)PV_SHORT_ROW_KEYS);
-  // the query pair of this wave's first head and the row's position are requested up front as well
-  const bool on = lane < HALF;
-  const int c = on ? lane : 0;
-  const int64_t g_row = caller_row(plan, h, g);        // this row in q / out / lse
-  const uint16_t* q_first = a.q + (g_row * a.hq + kvh * G + min(wave, G - 1)) * D;
-  const unsigned short q_lo0 = q_first[c], q_hi0 = q_first[c + HALF];
-  const int pos_g = plan[h.off_pos + g];
-  // all loads of the pass are issued before any of them is used (fixed trip count, predicated)
-  constexpr int IT = PV_SHORT_ROW_KEYS * HALF / 256;
-  static_assert(IT * 256 == PV_SHORT_ROW_KEYS * HALF, "whole passes");
-  unsigned short k_lo[IT], k_hi[IT], v_lo[IT], v_hi[IT];
-  int pos_k[IT];
-#pragma unroll
-  for (int it = 0; it < IT; ++it) {
-    const int item = tid + it * 256;
-    const int e = item / HALF, c = item % HALF;
-    const int key = e < n_a ? e : b0 + (e - n_a);
-    const int tok = base + (e < n ? key : i);             // clamp to a valid row when predicated off
-    const int64_t tok_row = src.row(caller_row(plan, h, tok));
-    const uint16_t* kr = src.k + (tok_row * hkv + kvh) * D;
-    const uint16_t* vr = src.v + (tok_row * hkv + kvh) * D;
-    k_lo[it] = kr[c]; k_hi[it] = kr[c + HALF];
-    v_lo[it] = vr[c]; v_hi[it] = vr[c + HALF];
-    pos_k[it] = plan[h.off_pos + tok];
-  }
-#pragma unroll
-  for (int it = 0; it < IT; ++it) {
-    const int item = tid + it * 256;
-    const int e = item / HALF, c = item % HALF;
-    if (e < n) {
-      const float xl = __uint_as_float((unsigned)k_lo[it] << 16), xh = __uint_as_float((unsigned)k_hi[it] << 16);
-      float rl = xl, rh = xh;
-      if (rope) {
-        const float2 t = rotary_cos_sin(pos_k[it], f.inv_freq[c]);
-        rl = xl * t.x - xh * t.y;
-        rh = xh * t.x + xl * t.y;
-      }
-      ks[e][c] = rl; ks[e][c + HALF] = rh;
-      vs[e][c] = __uint_as_float((unsigned)v_lo[it] << 16);
-      vs[e][c + HALF] = __uint_as_float((unsigned)v_hi[it] << 16);
-    }
-  }
-  __syncthreads();
-  const float2 t_g = rope ? rotary_cos_sin(pos_g, f.inv_freq[c]) : make_float2(1.0f, 0.0f);
-  for (int hl = wave; hl < G; hl += 4) {
-    const int head = kvh * G + hl;
-    const uint16_t* qr = a.q + (g_row * a.hq + head) * D;
-    const unsigned short q_lo = hl == wave ? q_lo0 : qr[c], q_hi = hl == wave ? q_hi0 : qr[c + HALF];
-    const float xl = __uint_as_float((unsigned)q_lo << 16), xh = __uint_as_float((unsigned)q_hi << 16);
-    const float ql = xl * t_g.x - xh * t_g.y, qh = xh * t_g.x + xl * t_g.y;
-    float sc[PV_SHORT_ROW_KEYS];
-    float m = -INFINITY;
-#pragma unroll
-    for (int e = 0; e < PV_SHORT_ROW_KEYS; ++e) {
-      float part = (on && e < n) ? ql * ks[e][c] + qh * ks[e][c + HALF] : 0.0f;
-#pragma unroll
-      for (int off = 32; off > 0; off >>= 1) part += __shfl_xor(part, off);
-      sc[e] = e < n ? part * a.scale : -INFINITY;
-      m = fmaxf(m, sc[e]);
-    }
-    float l = 0.0f, ol = 0.0f, oh = 0.0f;
-#pragma unroll
-    for (int e = 0; e < PV_SHORT_ROW_KEYS; ++e) {
-      const float p = expf(sc[e] - m);                  // exp(-inf) = 0 for the unused slots
-      l += p;
-      if (e < n) {
-        ol = fmaf(p, vs[e][c], ol);
-        oh = fmaf(p, vs[e][c + HALF], oh);
-      }
-    }
-    if (on) {
-      const int64_t row = (g_row * a.hq + head) * D;
-      if (a.out_f32) {
-        float* op = reinterpret_cast<float*>(a.out) + row;
-        op[c] = ol / l; op[c + HALF] = oh / l;
-      } else {
-        uint16_t* op = reinterpret_cast<uint16_t*>(a.out) + row;
-        op[c] = (uint16_t)(pack_bf16(ol / l, 0.0f) & 0xffffu);
-        op[c + HALF] = (uint16_t)(pack_bf16(oh / l, 0.0f) & 0xffffu);
-      }
-      if (a.lse && lane == 0) a.lse[(int64_t)head * h.total_tokens + g_row] = m + logf(l);
-    }
-  }
-}
-
 // grid = one block per (short row, kv head) first (they take longest, so they start first), then
 // blocks of 16 keys x 2 kv heads.  Pad rows (beyond the request) are written as 0 so that masked
 // probabilities (exactly 0) never meet a non-finite value.
@@ -178,7 +52,7 @@ __global__ __launch_bounds__(256) void k_prep_kv(const int32_t* __restrict__ pla
     const int4 desc = reinterpret_cast<const int4*>(plan + h.off_short)[idx / hkv];
     const int kvh = idx % hkv;
     float (*ks)[D] = reinterpret_cast<float (*)[D]>(&lds[0]);
-    short_row_block<D>(plan, h, src, f, hkv, rope, sr, desc, kvh, ks, ks + PV_SHORT_ROW_KEYS);
+    short_row_block<D, 4>(plan, h, src, &f, hkv, rope, sr, desc, kvh, ks, ks + PV_SHORT_ROW_KEYS);
     return;
   }
   float2 (*cs_s)[HALF] = reinterpret_cast<float2 (*)[HALF]>(&lds[0]);                       // cos/sin of the block's tokens
@@ -379,22 +253,26 @@ template <int D, int G>
 hipError_t launch_main(const int32_t* plan, const PlanHeader& h, const uint16_t* q,
                        const uint16_t* krot, const uint16_t* vt, const float2* cs, void* out,
                        float* lse, int hq, int hkv, float qscale, bool rope, bool out_f32,
-                       int split, float* part, hipStream_t s);
+                       int split, float* part, const KvSource& raw_kv, float scale, int n_short,
+                       hipStream_t s);
 template <int D>
 hipError_t launch_query_tiles(const int32_t* plan, const PlanHeader& h, const uint16_t* q,
                               const uint16_t* krot, const uint16_t* vt, const float2* cs,
                               void* out, float* lse, int hq, int hkv, float qscale, bool rope,
-                              bool out_f32, hipStream_t s);
+                              bool out_f32, const KvSource& raw_kv, float scale, int n_short,
+                              hipStream_t s);
 
 template <int D>
 static hipError_t dispatch_g(int G, const int32_t* plan, const PlanHeader& h, const uint16_t* q,
                              const uint16_t* krot, const uint16_t* vt, const float2* cs, void* out,
                              float* lse, int hq, int hkv, float qscale, bool rope, bool out_f32,
-                             int split, float* part, hipStream_t s) {
+                             int split, float* part, const KvSource& raw_kv, float scale, int n_short,
+                             hipStream_t s) {
   if (split == 0 && group_uses_query_tiles(G) && h.n_quads > 0)
-    return launch_query_tiles<D>(plan, h, q, krot, vt, cs, out, lse, hq, hkv, qscale, rope, out_f32, s);
+    return launch_query_tiles<D>(plan, h, q, krot, vt, cs, out, lse, hq, hkv, qscale, rope, out_f32, raw_kv,
+                                 scale, n_short, s);
   switch (G) {
-#define PV_CASE(GG) case GG: return launch_main<D, GG>(plan, h, q, krot, vt, cs, out, lse, hq, hkv, qscale, rope, out_f32, split, part, s);
+#define PV_CASE(GG) case GG: return launch_main<D, GG>(plan, h, q, krot, vt, cs, out, lse, hq, hkv, qscale, rope, out_f32, split, part, raw_kv, scale, n_short, s);
     PV_CASE(1) PV_CASE(2) PV_CASE(3) PV_CASE(4) PV_CASE(5) PV_CASE(6) PV_CASE(7) PV_CASE(8)
 #undef PV_CASE
   }
@@ -417,7 +295,7 @@ hipError_t launch_prep_bf16(const int32_t* plan_dev, const PlanHeader& h, const 
   src.page_size = kv.page_size;
   ShortRowArgs sr;
   sr.q = reinterpret_cast<const uint16_t*>(q); sr.out = out; sr.lse = lse; sr.hq = hq; sr.scale = scale;
-  sr.out_f32 = out_f32; sr.seg_only = segments_only;
+  sr.out_f32 = out_f32; sr.seg_only = segments_only; sr.table = nullptr;
   const int64_t n_short = q ? (int64_t)h.n_short_rows * hkv : 0;
   const int64_t n_key = key_blocks ? (int64_t)(h.padded_keys / 16) * ((hkv + 1) / 2) : 0;
   if (n_short + n_key == 0) return hipSuccess;
@@ -429,11 +307,20 @@ hipError_t launch_prep_bf16(const int32_t* plan_dev, const PlanHeader& h, const 
   return hipGetLastError();
 }
 
+// True when the main kernel's launch can carry the rows with few keys itself (as extra workgroups of
+// at least four waves at the end of a whole-pass grid).
+bool main_kernel_takes_short_rows(const PlanHeader& h, int hq, int hkv, bool segments_only) {
+  const int G = hq / hkv;
+  if (segments_only || h.n_short_rows == 0) return false;
+  return (group_uses_query_tiles(G) && h.n_quads > 0) || G >= 4;
+}
+
 // The main kernel over prepared keys (and the merge of the key pieces of the segment-only call).
+// short_rows_kv != nullptr: the launch also evaluates the rows with few keys from these K/V tensors.
 hipError_t launch_main_bf16(const int32_t* plan_dev, const PlanHeader& h, const void* q, void* out,
                             float* lse, int hq, int hkv, int d, int out_dtype, float scale, bool rope,
-                            char* ws, const AttnWorkspace& wl, bool segments_only, hipEvent_t ev0,
-                            hipEvent_t ev1, hipStream_t s) {
+                            char* ws, const AttnWorkspace& wl, bool segments_only,
+                            const KvArgs* short_rows_kv, hipEvent_t ev0, hipEvent_t ev1, hipStream_t s) {
   if (segments_only && h.n_seg_tiles == 0) return hipSuccess;          // no segment anywhere
   float2* cs = reinterpret_cast<float2*>(ws + wl.off_cs);
   uint16_t* krot = reinterpret_cast<uint16_t*>(ws + wl.off_krot);
@@ -444,9 +331,19 @@ hipError_t launch_main_bf16(const int32_t* plan_dev, const PlanHeader& h, const 
   hipError_t e;
   const float qscale = scale * 1.4426950408889634f;
   const int split = segments_only ? wl.split : 0;
+  KvSource raw_kv = {nullptr, nullptr, nullptr, 1};
+  int64_t n_short = 0;
+  if (short_rows_kv) {
+    raw_kv.k = reinterpret_cast<const uint16_t*>(short_rows_kv->k);
+    raw_kv.v = reinterpret_cast<const uint16_t*>(short_rows_kv->v);
+    raw_kv.block_table = short_rows_kv->block_table;
+    raw_kv.page_size = short_rows_kv->page_size;
+    n_short = (int64_t)h.n_short_rows * hkv;
+    if (n_short > 0x7fffffff) return hipErrorInvalidConfiguration;
+  }
   if (ev0) { e = hipEventRecord(ev0, s); if (e != hipSuccess) return e; }
-  if (d == 64) e = dispatch_g<64>(hq / hkv, plan_dev, h, kq, krot, vt, cs, out, lse, hq, hkv, qscale, rope, out_f32, split, part, s);
-  else e = dispatch_g<128>(hq / hkv, plan_dev, h, kq, krot, vt, cs, out, lse, hq, hkv, qscale, rope, out_f32, split, part, s);
+  if (d == 64) e = dispatch_g<64>(hq / hkv, plan_dev, h, kq, krot, vt, cs, out, lse, hq, hkv, qscale, rope, out_f32, split, part, raw_kv, scale, (int)n_short, s);
+  else e = dispatch_g<128>(hq / hkv, plan_dev, h, kq, krot, vt, cs, out, lse, hq, hkv, qscale, rope, out_f32, split, part, raw_kv, scale, (int)n_short, s);
   if (e != hipSuccess) return e;
   if (ev1) { e = hipEventRecord(ev1, s); if (e != hipSuccess) return e; }
   if (split > 1) {

@@ -13,7 +13,8 @@ namespace pv {
 #define PV_INST(GG)                                                                               \
   template hipError_t launch_main<PV_INST_D, GG>(                                                 \
       const int32_t*, const PlanHeader&, const uint16_t*, const uint16_t*, const uint16_t*,       \
-      const float2*, void*, float*, int, int, float, bool, bool, int, float*, hipStream_t);
+      const float2*, void*, float*, int, int, float, bool, bool, int, float*, const KvSource&, float,  \
+      int, hipStream_t);
 
 #if PV_INST_SET >= 1 && PV_INST_SET <= 8
 PV_INST(PV_INST_SET)
@@ -21,7 +22,7 @@ PV_INST(PV_INST_SET)
 template hipError_t launch_query_tiles<PV_INST_D>(const int32_t*, const PlanHeader&, const uint16_t*,
                                                   const uint16_t*, const uint16_t*, const float2*,
                                                   void*, float*, int, int, float, bool, bool,
-                                                  hipStream_t);
+                                                  const KvSource&, float, int, hipStream_t);
 #else
 #error "PV_INST_SET must be 1..9"
 #endif

@@ -6,6 +6,7 @@
 #define PV_ATTN_BF16_MAIN_H_
 
 #include "pv_attn_common.h"
+#include "pv_short_rows.h"
 
 namespace pv {
 
@@ -22,7 +23,8 @@ __global__ __launch_bounds__(G * 64, 2) __attribute__((amdgpu_waves_per_eu(2))) 
     const int32_t* __restrict__ plan, PlanHeader h, const uint16_t* __restrict__ q,
     const uint16_t* __restrict__ krot, const uint16_t* __restrict__ vt,
     const float2* __restrict__ cs, void* __restrict__ out, float* __restrict__ lse, int hq, int hkv,
-    float qscale, bool rope, bool out_f32, int split, float* __restrict__ part) {
+    float qscale, bool rope, bool out_f32, int split, float* __restrict__ part, KvSource raw_kv,
+    float scale, int n_short_blocks) {
   constexpr int KT = D / 16;            // MFMA steps along the feature dim for S^T
   constexpr int DB = D / 32;            // 32-feature blocks of O^T
   constexpr int CH32 = 32 * D / 8;      // 16-byte chunks per 32-key K (or V^T) slot
@@ -35,6 +37,23 @@ __global__ __launch_bounds__(G * 64, 2) __attribute__((amdgpu_waves_per_eu(2))) 
   // the staging pipeline.  Ordering is enforced here with explicit vmcnt waits and barriers.
   // Layout: K ring (NS slots), then V^T ring (NS slots).  Step s lives in slot s % NS of each.
   __shared__ uint4 smem[2 * NS * CH32];
+
+  // The last n_short_blocks workgroups of a whole-pass launch evaluate the rows with very few keys
+  // in fp32, one (row, kv head) each, from the caller's K/V and the table of rotary angles.  They
+  // are light and start when the grid's items are all taken, in the tail of the launch.
+  if constexpr (G >= 4) {
+    if (n_short_blocks > 0 && blockIdx.x >= gridDim.x - (unsigned)n_short_blocks) {
+      static_assert(2 * PV_SHORT_ROW_KEYS * D * 4 <= sizeof(smem), "short-row tiles must fit");
+      const int idx = (int)(blockIdx.x - (gridDim.x - (unsigned)n_short_blocks));
+      const int4 desc = reinterpret_cast<const int4*>(plan + h.off_short)[idx / hkv];
+      ShortRowArgs a;
+      a.q = q; a.out = out; a.lse = lse; a.hq = hq; a.scale = scale; a.out_f32 = out_f32;
+      a.seg_only = false; a.table = cs;
+      float (*ks)[D] = reinterpret_cast<float (*)[D]>(&smem[0]);
+      short_row_block<D, G>(plan, h, raw_kv, nullptr, hkv, rope, a, desc, idx % hkv, ks, ks + PV_SHORT_ROW_KEYS);
+      return;
+    }
+  }
 
   // split == 0: the whole pass, one workgroup per entry of the work list and kv head.
   // split >= 1: segment rows only, one workgroup per (tile holding segment rows, kv head, piece);
@@ -65,7 +84,6 @@ __global__ __launch_bounds__(G * 64, 2) __attribute__((amdgpu_waves_per_eu(2))) 
   }
   const bool valid = qrow < mine.rows;
   const int64_t g = (int64_t)mine.tok_base + mine.t0 + qrow;
-  const int i_loc = valid ? mine.t0 + qrow : -1;
   int a_end = 0, b_start = 0;
   if (valid) { a_end = plan[h.off_aend + g]; b_start = plan[h.off_bstart + g]; }
 
@@ -98,6 +116,15 @@ __global__ __launch_bounds__(G * 64, 2) __attribute__((amdgpu_waves_per_eu(2))) 
   // a plain copy and operand reads are linear (lane l reads chunk l of its k-step: no conflicts).
   constexpr int NREP = (CH32 / 64 + G - 1) / G;                  // staging instructions per wave
   const unsigned lane16 = (unsigned)lane * 16;
+  // the row's own index in its request (-1: no row).  Recomputed where it is needed, in the mask
+  // code and the epilogue, from a lane index the compiler cannot hoist: the register file is full,
+  // and a value that lives through the loops for the sake of a rare path ends up in scratch memory.
+  auto own_row = [&]() {
+    unsigned l16 = lane16;
+    asm volatile("" : "+v"(l16));
+    const int r = (int)((l16 >> 4) & 31u);
+    return r < mine.rows ? mine.t0 + r : -1;
+  };
   const unsigned smem_base =
       (unsigned)(uintptr_t)(__attribute__((address_space(3))) char*)(char*)&smem[0];
   const unsigned vring = smem_base + NS * SLOT_BYTES;
@@ -200,6 +227,7 @@ __global__ __launch_bounds__(G * 64, 2) __attribute__((amdgpu_waves_per_eu(2))) 
       const unsigned m = (1u << (n & 31)) - 1u;
       return n <= 0 ? 0u : n >= 32 ? 0xffffffffu : m;
     };
+    const int i_loc = own_row();
     const unsigned vis = low_bits(a_end - base) | (low_bits(i_loc - base + 1) & ~low_bits(b_start - base));
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
@@ -702,7 +730,7 @@ __global__ __launch_bounds__(G * 64, 2) __attribute__((amdgpu_waves_per_eu(2))) 
     // (lane r < 32 holds the descriptor of row r: one ballot gives the row mask to every lane);
     // the segment-only call stores segment rows only (b_start > 0 marks them)
     const unsigned stored_rows = (unsigned)__builtin_amdgcn_ballot_w64(
-        valid && a_end + i_loc - b_start + 1 > PV_SHORT_ROW_KEYS && (split == 0 || b_start > 0));
+        valid && a_end + own_row() - b_start + 1 > PV_SHORT_ROW_KEYS && (split == 0 || b_start > 0));
     auto stored = [&](int row) { return partial || ((stored_rows >> row) & 1u) != 0; };
     constexpr int RS = 2 * D + 16;                    // row stride: 16 B of padding spreads the banks
     char* tr = reinterpret_cast<char*>(&smem[0]) + (size_t)wave * (32 * RS);
@@ -762,16 +790,19 @@ template <int D, int G>
 hipError_t launch_main(const int32_t* plan, const PlanHeader& h, const uint16_t* q,
                               const uint16_t* krot, const uint16_t* vt, const float2* cs, void* out,
                               float* lse, int hq, int hkv, float qscale, bool rope, bool out_f32,
-                              int split, float* part, hipStream_t s) {
+                              int split, float* part, const KvSource& raw_kv, float scale, int n_short,
+                              hipStream_t s) {
   dim3 grid;
-  const int64_t blocks = split ? (int64_t)h.n_seg_tiles * hkv * split : (int64_t)h.n_q_tiles * hkv;
+  const int64_t blocks = (split ? (int64_t)h.n_seg_tiles * hkv * split : (int64_t)h.n_q_tiles * hkv) + n_short;
   if (!grid_1d(blocks, G * 64, &grid)) return hipErrorInvalidConfiguration;
   if (rope)
     k_attn_bf16<D, G, true><<<grid, dim3(G * 64), 0, s>>>(plan, h, q, krot, vt, cs, out, lse, hq, hkv,
-                                                          qscale, rope, out_f32, split, part);
+                                                          qscale, rope, out_f32, split, part, raw_kv, scale,
+                                                          n_short);
   else
     k_attn_bf16<D, G, false><<<grid, dim3(G * 64), 0, s>>>(plan, h, q, krot, vt, cs, out, lse, hq, hkv,
-                                                           qscale, rope, out_f32, split, part);
+                                                           qscale, rope, out_f32, split, part, raw_kv, scale,
+                                                           n_short);
   return hipGetLastError();
 }
 
@@ -780,15 +811,18 @@ template <int D>
 hipError_t launch_query_tiles(const int32_t* plan, const PlanHeader& h, const uint16_t* q,
                                      const uint16_t* krot, const uint16_t* vt, const float2* cs,
                                      void* out, float* lse, int hq, int hkv, float qscale, bool rope,
-                                     bool out_f32, hipStream_t s) {
+                                     bool out_f32, const KvSource& raw_kv, float scale, int n_short,
+                                     hipStream_t s) {
   dim3 grid;
-  if (!grid_1d((int64_t)h.n_quads * hq, 256, &grid)) return hipErrorInvalidConfiguration;
+  if (!grid_1d((int64_t)h.n_quads * hq + n_short, 256, &grid)) return hipErrorInvalidConfiguration;
   if (rope)
     k_attn_bf16<D, 4, true, true><<<grid, dim3(256), 0, s>>>(plan, h, q, krot, vt, cs, out, lse, hq, hkv,
-                                                             qscale, rope, out_f32, 0, nullptr);
+                                                             qscale, rope, out_f32, 0, nullptr, raw_kv, scale,
+                                                             n_short);
   else
     k_attn_bf16<D, 4, false, true><<<grid, dim3(256), 0, s>>>(plan, h, q, krot, vt, cs, out, lse, hq, hkv,
-                                                              qscale, rope, out_f32, 0, nullptr);
+                                                              qscale, rope, out_f32, 0, nullptr, raw_kv, scale,
+                                                              n_short);
   return hipGetLastError();
 }
 

@@ -128,10 +128,13 @@ hipError_t launch_prep_bf16(const int32_t* plan_dev, const PlanHeader& h, const 
                             float* lse, int hq, float scale, bool out_f32, bool segments_only,
                             hipStream_t s);
 // bf16 path, step 2: the main kernel over the prepared keys (whole pass, or segment rows only).
+// short_rows_kv != nullptr: the launch also evaluates the rows with few keys (fp32) from these tensors,
+// which main_kernel_takes_short_rows says it can; otherwise the preparation launch has done them.
+bool main_kernel_takes_short_rows(const PlanHeader& h, int hq, int hkv, bool segments_only);
 hipError_t launch_main_bf16(const int32_t* plan_dev, const PlanHeader& h, const void* q, void* out,
                             float* lse, int hq, int hkv, int d, int out_dtype, float scale, bool rope,
-                            char* ws, const AttnWorkspace& wl, bool segments_only, hipEvent_t ev0,
-                            hipEvent_t ev1, hipStream_t s);
+                            char* ws, const AttnWorkspace& wl, bool segments_only,
+                            const KvArgs* short_rows_kv, hipEvent_t ev0, hipEvent_t ev1, hipStream_t s);
 
 // FP8 K/V path (head_dim 128): preparation, short rows and the main kernel on the FP8 matrix instruction.
 hipError_t launch_attn_fp8(const int32_t* plan_dev, const PlanHeader& h, const void* q, const void* k8,
