@@ -4,7 +4,8 @@
 // FP8 matrix instruction v_mfma_f32_32x32x64_f8f6f4 (64-deep, twice the bf16 rate), fp32 accumulate:
 //   k_prep_fp8   K and V^T of every 64-key tile re-laid-out in MFMA operand order (plain byte moves,
 //                no arithmetic on the codes), and the cos/sin table for Q
-//   k_short_fp8  rows that see at most PV_SHORT_ROW_KEYS keys, in plain fp32
+//   (rows that see at most PV_SHORT_ROW_KEYS keys are evaluated in plain fp32 by extra workgroups at the
+//   end of k_attn_fp8's grid, one wave per row and query head)
 //   k_attn_fp8   flash-style pass: one workgroup = one 32-token query tile x one kv head, wave w =
 //                query head kvh*G + w; a step is one 64-key tile.  Q is rotated, scaled by a per-row
 //                power of two and split into two E4M3 terms (the rounded value and 16 x the rounding
@@ -126,18 +127,13 @@ __global__ __launch_bounds__(256) void k_prep_fp8(const int32_t* __restrict__ pl
 // ---------------------------------------------------------------- rows with few keys, fp32
 // One wave per (short row, query head); lane c owns the rotation pair (c, c + D/2).
 template <int D>
-__global__ __launch_bounds__(256) void k_short_fp8(const int32_t* __restrict__ plan, PlanHeader h,
-                                                   const uint16_t* __restrict__ q,
-                                                   const uint8_t* __restrict__ k8,
-                                                   const uint8_t* __restrict__ v8,
-                                                   const float* __restrict__ k_scale,
-                                                   const float* __restrict__ v_scale, RopeFreq f,
-                                                   int hq, int hkv, bool rope, float scale,
-                                                   void* __restrict__ out, float* __restrict__ lse,
-                                                   bool out_f32) {
+__device__ void short_unit_fp8(const int32_t* __restrict__ plan, const PlanHeader& h,
+                               const uint16_t* __restrict__ q, const uint8_t* __restrict__ k8,
+                               const uint8_t* __restrict__ v8, const float* __restrict__ k_scale,
+                               const float* __restrict__ v_scale, const float2* __restrict__ table,
+                               int hq, int hkv, bool rope, float scale, void* __restrict__ out,
+                               float* __restrict__ lse, bool out_f32, int unit, int lane) {
   constexpr int HALF = D / 2;
-  const int unit = (int)blockIdx.x * 4 + ((int)threadIdx.x >> 6), lane = threadIdx.x & 63;
-  if (unit >= h.n_short_rows * hq) return;                 // whole waves leave together
   const int4 desc = reinterpret_cast<const int4*>(plan + h.off_short)[unit / hq];
   const int head = unit % hq, kvh = head / (hq / hkv);
   const int g = desc.x, base = desc.y, i = g - base, a_end = desc.z, b_start = desc.w;
@@ -150,7 +146,7 @@ __global__ __launch_bounds__(256) void k_short_fp8(const int32_t* __restrict__ p
   const float xl = __uint_as_float((unsigned)qr[c] << 16), xh = __uint_as_float((unsigned)qr[c + HALF] << 16);
   float ql = xl, qh = xh;
   if (rope) {
-    const float2 t = rotary_cos_sin(plan[h.off_pos + g], f.inv_freq[c]);
+    const float2 t = table[(int64_t)g * HALF + c];
     ql = xl * t.x - xh * t.y;
     qh = xh * t.x + xl * t.y;
   }
@@ -219,8 +215,19 @@ __global__ __launch_bounds__(G * 64, 2) void k_attn_fp8(
     const int32_t* __restrict__ plan, PlanHeader h, const uint16_t* __restrict__ q,
     const uint8_t* __restrict__ kw, const uint8_t* __restrict__ vw, const float2* __restrict__ cs,
     const float* __restrict__ k_scale, const float* __restrict__ v_scale, void* __restrict__ out,
-    float* __restrict__ lse, int hq, int hkv, float qscale, bool rope, bool out_f32) {
+    float* __restrict__ lse, int hq, int hkv, float qscale, bool rope, bool out_f32,
+    const uint8_t* __restrict__ k8, const uint8_t* __restrict__ v8, float scale, int n_short_blocks) {
   static_assert(D == 128, "the FP8 path is built for head_dim 128");
+  // The last n_short_blocks workgroups evaluate the rows with very few keys in fp32, one (row, query
+  // head) per wave, from the caller's codes and the table of rotary angles: light work that starts
+  // when every item of the grid has been taken, in the tail of the launch.
+  if (n_short_blocks > 0 && blockIdx.x >= gridDim.x - (unsigned)n_short_blocks) {
+    const int unit = (int)(blockIdx.x - (gridDim.x - (unsigned)n_short_blocks)) * G + ((int)threadIdx.x >> 6);
+    if (unit < h.n_short_rows * hq)                        // whole waves leave together
+      short_unit_fp8<D>(plan, h, q, k8, v8, k_scale, v_scale, cs, hq, hkv, rope, scale, out, lse, out_f32,
+                        unit, (int)threadIdx.x & 63);
+    return;
+  }
   constexpr int TILE_BYTES = kStepKeys * D;               // 8 KB of K, the same of V^T
   constexpr int TILE_CHUNKS = TILE_BYTES / 16;            // 512
   constexpr int CPT = (2 * TILE_CHUNKS + G * 64 - 1) / (G * 64);   // staging chunks per thread and step
@@ -401,7 +408,7 @@ __global__ __launch_bounds__(G * 64, 2) void k_attn_fp8(
 
   // ---- epilogue: every register of lacc holds the row sum of this lane's query column
   const float l_tot = lacc[0];
-  const bool stored = valid && a_end + i_loc - b_start + 1 > PV_SHORT_ROW_KEYS;   // short rows: k_short_fp8
+  const bool stored = valid && a_end + i_loc - b_start + 1 > PV_SHORT_ROW_KEYS;   // short rows: the extra workgroups
   if (stored) {
     const float inv = v_scale[kvh] / l_tot;
     const int64_t orow = (caller_row(plan, h, g) * hq + head) * D;
@@ -427,10 +434,15 @@ __global__ __launch_bounds__(G * 64, 2) void k_attn_fp8(
 template <int G>
 static hipError_t launch_main_fp8(const int32_t* plan, const PlanHeader& h, const uint16_t* q, const uint8_t* kw,
                                   const uint8_t* vw, const float2* cs, const float* ks, const float* vs, void* out,
-                                  float* lse, int hq, int hkv, float qscale, bool rope, bool out_f32, hipStream_t s) {
+                                  float* lse, int hq, int hkv, float qscale, bool rope, bool out_f32,
+                                  const uint8_t* k8, const uint8_t* v8, float scale, hipStream_t s) {
   dim3 grid;
-  if (!grid_1d((int64_t)h.n_q_tiles * hkv, G * 64, &grid)) return hipErrorInvalidConfiguration;
-  k_attn_fp8<128, G><<<grid, dim3(G * 64), 0, s>>>(plan, h, q, kw, vw, cs, ks, vs, out, lse, hq, hkv, qscale, rope, out_f32);
+  // one wave per (short row, query head), G of them to a workgroup, behind the items of the grid
+  const int64_t n_short = ((int64_t)h.n_short_rows * hq + G - 1) / G;
+  if (n_short > 0x7fffffff || !grid_1d((int64_t)h.n_q_tiles * hkv + n_short, G * 64, &grid))
+    return hipErrorInvalidConfiguration;
+  k_attn_fp8<128, G><<<grid, dim3(G * 64), 0, s>>>(plan, h, q, kw, vw, cs, ks, vs, out, lse, hq, hkv, qscale, rope,
+                                                   out_f32, k8, v8, scale, (int)n_short);
   return hipGetLastError();
 }
 
@@ -449,17 +461,10 @@ hipError_t launch_attn_fp8(const int32_t* plan_dev, const PlanHeader& h, const v
   k_prep_fp8<128><<<grid, dim3(256), 0, s>>>(plan_dev, h, (const uint8_t*)k8, (const uint8_t*)v8, freq, cs, hkv, rope, kw, vw);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  if (h.n_short_rows > 0) {
-    if (!grid_1d(((int64_t)h.n_short_rows * hq + 3) / 4, 256, &grid)) return hipErrorInvalidConfiguration;
-    k_short_fp8<128><<<grid, dim3(256), 0, s>>>(plan_dev, h, kq, (const uint8_t*)k8, (const uint8_t*)v8, k_scale, v_scale,
-                                                freq, hq, hkv, rope, scale, out, lse, out_f32);
-    e = hipGetLastError();
-    if (e != hipSuccess) return e;
-  }
   const float qscale = scale * 1.4426950408889634f;
   if (ev0) { e = hipEventRecord(ev0, s); if (e != hipSuccess) return e; }
   switch (hq / hkv) {
-#define PV_CASE(GG) case GG: e = launch_main_fp8<GG>(plan_dev, h, kq, kw, vw, cs, k_scale, v_scale, out, lse, hq, hkv, qscale, rope, out_f32, s); break;
+#define PV_CASE(GG) case GG: e = launch_main_fp8<GG>(plan_dev, h, kq, kw, vw, cs, k_scale, v_scale, out, lse, hq, hkv, qscale, rope, out_f32, (const uint8_t*)k8, (const uint8_t*)v8, scale, s); break;
     PV_CASE(1) PV_CASE(2) PV_CASE(3) PV_CASE(4) PV_CASE(5) PV_CASE(6) PV_CASE(7) PV_CASE(8)
 #undef PV_CASE
     default: e = hipErrorInvalidValue;
