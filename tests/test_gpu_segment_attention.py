@@ -235,3 +235,35 @@ def test_prepared_8b_and_argument_checks():
         with pytest.raises(pv.PvError) as e:
             pv.pv_prepare_kv(ver.sizes, ver.plan, k, v, ver.workspace, rope_theta=w.rope_theta, **bad)
         assert e.value.status == pv.PV_ERR_SHAPE, bad
+
+
+# The rows with very few visible keys are evaluated in fp32 by one piece of code in two places: extra
+# workgroups of the main kernel's launch in a whole pass (rotary angles read from the table), blocks of
+# the preparation launch in the segment-only call (angles computed on the spot).  Segment rows that see
+# almost nothing must come out of both with the same bits.
+@pytest.mark.parametrize("d,group", [(128, 4), (128, 8), (64, 4), (128, 5)])
+def test_short_segment_rows_same_bits_in_both_calls(d, group):
+    pr = wl.Problem([0, 3], [40, 9], [4, 2], [6, 20], [[0, 1, 2, 40], [0, 5]])
+    w = wl.make_custom(pr, 2 * group, 2, d, dtype=torch.bfloat16, rope_theta=5e5, seed=4242 + d + group)
+    ver = gc.make_verifier(pv, w)
+    ver.build_mask()
+    assert ver.sizes.n_short_seg_rows > 0
+    dev = ver.device
+    q, k, v = w.q.to(dev), w.k.to(dev), w.v.to(dev)
+    seg = torch.from_numpy(gc.packed_row_index(pr, segment_rows(pr))).to(dev)
+    for dt in (torch.float32, torch.bfloat16):
+        full = torch.zeros(q.shape, dtype=dt, device=dev)
+        lse_full = torch.zeros((w.n_q_heads, pr.total_tokens), dtype=torch.float32, device=dev)
+        ver.attention(q, k, v, out=full, lse=lse_full, rope_theta=w.rope_theta)
+        only = torch.zeros(q.shape, dtype=dt, device=dev)
+        lse_only = torch.zeros((w.n_q_heads, pr.total_tokens), dtype=torch.float32, device=dev)
+        ver.segment_attention(q, k, v, only, lse=lse_only, rope_theta=w.rope_theta)
+        torch.cuda.synchronize()
+        a, b = full.index_select(0, seg), only.index_select(0, seg)
+        la, lb = lse_full.index_select(1, seg), lse_only.index_select(1, seg)
+        # at least the segment rows that the plan lists as short must agree bit for bit
+        plan_short = ver.sizes.n_short_seg_rows
+        same_rows = (a.view(a.shape[0], -1) == b.view(b.shape[0], -1)).all(dim=1)
+        assert int(same_rows.sum()) >= plan_short, (int(same_rows.sum()), plan_short)
+        same_lse = (la == lb).all(dim=0)
+        assert int(same_lse.sum()) >= plan_short
