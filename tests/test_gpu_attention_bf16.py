@@ -269,3 +269,29 @@ def test_k0_is_plain_causal_matches_library():
     ref = torch.nn.functional.scaled_dot_product_attention(q, k, v, is_causal=True)[0].permute(1, 0, 2)
     err = (out - ref).abs()
     assert err.max().item() <= MAX_ABS and err.mean().item() <= MEAN_ABS
+
+
+def random_long_problem(rng):
+    B = int(rng.integers(1, 3))
+    P = [int(x) for x in rng.integers(0, 1200, B)]
+    T = [int(x) for x in rng.integers(1, 900, B)]
+    K = [int(x) for x in rng.integers(0, 6, B)]
+    S = [int(rng.choice([1, 5, 16, 33, 47, 70])) for _ in range(B)]
+    bounds = [sorted(int(x) for x in rng.integers(0, T[b] + 1, K[b])) for b in range(B)]
+    return wl.Problem(P, T, K, S, bounds)
+
+
+@pytest.mark.parametrize("seed", range(16))
+def test_random_long_problems(seed):
+    # items of 20 to 65 steps: the unrolled periods of the main kernel, the steps left over behind them,
+    # the jump to a segment's own keys at a random place, every group size, both layouts
+    rng = np.random.default_rng(9000 + seed)
+    pr = random_long_problem(rng)
+    if seed % 3 == 2:
+        import dataclasses
+        pr = dataclasses.replace(pr, layout=1)
+    group = int(rng.integers(1, 9))
+    d = int(rng.choice([64, 128]))
+    theta = float(rng.choice([0.0, 5e5]))
+    w = wl.make_custom(pr, group, 1, d, dtype=torch.bfloat16, rope_theta=theta, seed=9100 + seed)
+    check_full(w)
